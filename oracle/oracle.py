@@ -1,0 +1,175 @@
+"""ctypes front end of the CPU oracle (``rose_oracle.c``).
+
+TEST INFRASTRUCTURE: imported only by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``.  The GPU library never imports
+this module and this module never imports the GPU library.
+
+A *tensor record* is a dict with keys
+  ``old``   numpy uint16 array of R*C bf16 bit patterns (W_{t-1})
+  ``new``   numpy uint16 array (bf16 patterns) or uint32/float32 array (fp32 master)
+  ``rows``, ``cols``, ``rule`` (0 replicated, 1 split rows, 2 split cols,
+  3 fused rows) and, for rule 3, ``sections`` (row count of each stacked part).
+
+A *bucket* (Sec. 4.2, COO data of one destination shard) is a dict with
+  ``idx``     int32 local indices, ``val`` uint16 new bit patterns,
+  ``seg_off`` int64 [n_tensors+1]: entries of tensor t are seg_off[t]:seg_off[t+1].
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rose_oracle.c")
+_LIB = os.path.join(_HERE, "librose_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C, no special flags beyond -O2)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fPIC", "-shared",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, i32 = ctypes.c_int64, ctypes.c_int
+        vp = ctypes.c_void_p
+        lib.orc_rne_bf16.restype = ctypes.c_uint16
+        lib.orc_rne_bf16.argtypes = [ctypes.c_uint32]
+        lib.orc_rne_bf16_array.restype = None
+        lib.orc_rne_bf16_array.argtypes = [vp, vp, i64]
+        lib.orc_local_numel.restype = i64
+        lib.orc_local_numel.argtypes = [i32, i64, i64, i32]
+        lib.orc_shard_map.restype = i32
+        lib.orc_shard_map.argtypes = [i32, i64, i64, i32, vp, i32, i64, i64, vp, vp, vp]
+        lib.orc_encode_tensor.restype = i32
+        lib.orc_encode_tensor.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, vp, vp, vp]
+        lib.orc_apply.restype = i32
+        lib.orc_apply.argtypes = [vp, vp, i64, vp, i64]
+        lib.orc_dense_shard.restype = i32
+        lib.orc_dense_shard.argtypes = [vp, i32, i64, i64, i32, vp, i32, i32, vp]
+        _lib = lib
+    return _lib
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(rc, what):
+    if rc != 0:
+        names = {1: "bad argument", 2: "bad shape", 3: "out of range", 4: "order violated"}
+        raise OracleError("%s: %s" % (what, names.get(rc, rc)))
+
+
+def _sections(sections):
+    sec = np.ascontiguousarray(np.asarray(sections if sections is not None else [], dtype=np.int64))
+    return sec, (sec.ctypes.data if sec.size else None)
+
+
+def rne_bf16(bits32):
+    """fp32 bit pattern(s) -> bf16 bit pattern(s), round to nearest even."""
+    lib = _load()
+    if np.isscalar(bits32):
+        return int(lib.orc_rne_bf16(int(bits32) & 0xFFFFFFFF))
+    a = np.ascontiguousarray(bits32).view(np.uint32).ravel()
+    out = np.empty(a.size, dtype=np.uint16)
+    lib.orc_rne_bf16_array(a.ctypes.data, out.ctypes.data, a.size)
+    return out
+
+
+def local_numel(rule, rows, cols, tp):
+    return int(_load().orc_local_numel(rule, rows, cols, tp))
+
+
+def shard_map(rule, rows, cols, sections, tp, r, c):
+    """-> (d_first, n_dest, local) of element (r, c)."""
+    sec, secp = _sections(sections)
+    d_first, n_dest, local = ctypes.c_int(), ctypes.c_int(), ctypes.c_int64()
+    rc = _load().orc_shard_map(rule, rows, cols, sec.size, secp, tp, r, c,
+                               ctypes.addressof(d_first), ctypes.addressof(n_dest),
+                               ctypes.addressof(local))
+    _check(rc, "shard_map")
+    return d_first.value, n_dest.value, local.value
+
+
+def encode_tensor(old, new, rows, cols, rule, sections, tp):
+    """Dense-to-sparse of one tensor -> list over shards of (idx int32, val uint16)."""
+    lib = _load()
+    old = np.ascontiguousarray(old).view(np.uint16).ravel()
+    new = np.ascontiguousarray(new).ravel()
+    if new.dtype.itemsize == 4:
+        new, is_f32 = new.view(np.uint32), 1
+    elif new.dtype.itemsize == 2:
+        new, is_f32 = new.view(np.uint16), 0
+    else:
+        raise OracleError("new must hold 16-bit or 32-bit patterns")
+    if old.size != rows * cols or new.size != rows * cols:
+        raise OracleError("array sizes do not match rows*cols")
+    sec, secp = _sections(sections)
+    counts = np.zeros(tp, dtype=np.int64)
+    rc = lib.orc_encode_tensor(old.ctypes.data, new.ctypes.data, is_f32, rule, rows, cols,
+                               sec.size, secp, tp, counts.ctypes.data, None, None)
+    _check(rc, "encode_tensor(count)")
+    idx = [np.empty(int(n), dtype=np.int32) for n in counts]
+    val = [np.empty(int(n), dtype=np.uint16) for n in counts]
+    pi = (ctypes.c_void_p * tp)(*[a.ctypes.data for a in idx])
+    pv = (ctypes.c_void_p * tp)(*[a.ctypes.data for a in val])
+    counts2 = np.zeros(tp, dtype=np.int64)
+    rc = lib.orc_encode_tensor(old.ctypes.data, new.ctypes.data, is_f32, rule, rows, cols,
+                               sec.size, secp, tp, counts2.ctypes.data, pi, pv)
+    _check(rc, "encode_tensor(fill)")
+    assert (counts == counts2).all()
+    return list(zip(idx, val))
+
+
+def encode_model(tensors, tp):
+    """All tensors -> one bucket per destination shard, segments in tensor order."""
+    per_tensor = [encode_tensor(t["old"], t["new"], t["rows"], t["cols"], t["rule"],
+                                t.get("sections"), tp) for t in tensors]
+    buckets = []
+    for d in range(tp):
+        seg_off = np.zeros(len(tensors) + 1, dtype=np.int64)
+        for i, segs in enumerate(per_tensor):
+            seg_off[i + 1] = seg_off[i] + segs[d][0].size
+        idx = np.concatenate([segs[d][0] for segs in per_tensor]) if tensors else np.empty(0, np.int32)
+        val = np.concatenate([segs[d][1] for segs in per_tensor]) if tensors else np.empty(0, np.uint16)
+        buckets.append({"idx": idx, "val": val, "seg_off": seg_off})
+    return buckets
+
+
+def apply_segment(idx, val, dst):
+    """Sparse-to-dense of one segment, in place on ``dst`` (uint16, flat local copy)."""
+    assert dst.dtype == np.uint16 and dst.flags["C_CONTIGUOUS"]
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=np.uint16)
+    rc = _load().orc_apply(idx.ctypes.data, val.ctypes.data, idx.size, dst.ctypes.data, dst.size)
+    _check(rc, "apply")
+
+
+def apply_bucket(bucket, dsts):
+    """Apply every segment of a bucket onto the receiver's local copies ``dsts[t]``."""
+    so = bucket["seg_off"]
+    for t, dst in enumerate(dsts):
+        a, b = int(so[t]), int(so[t + 1])
+        apply_segment(bucket["idx"][a:b], bucket["val"][a:b], dst)
+
+
+def dense_shard(full, rows, cols, rule, sections, tp, d):
+    """Shard d's local copy of a full tensor, through the shard map (dense path)."""
+    full = np.ascontiguousarray(full).view(np.uint16).ravel()
+    sec, secp = _sections(sections)
+    out = np.zeros(local_numel(rule, rows, cols, tp), dtype=np.uint16)
+    rc = _load().orc_dense_shard(full.ctypes.data, rule, rows, cols, sec.size, secp, tp, d,
+                                 out.ctypes.data)
+    _check(rc, "dense_shard")
+    return out

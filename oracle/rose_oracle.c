@@ -1,0 +1,224 @@
+/*
+ * CPU oracle for sparse weight-delta synchronisation (ROSE, Sec. 4.2,
+ * "Shard-aware Weight Transfer" and "Sparsity-aware Weight Transfer").
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, single-threaded
+ * statement of what the method computes, used only to check the GPU library
+ * and to be timed beside it as a baseline.  It shares no code, header, table
+ * or helper with the GPU library and must never be called from it.
+ *
+ * What the paper fixes (Sec. 4.2): the delta dW_t = W_t - W_{t-1} is sent in
+ * COO form, losslessly, only non-zero elements; the COO data is split by the
+ * receiver's parallel layout so that every receiving device applies only its
+ * own part onto its resident W_{t-1}; per-parameter shard rules are "sharded
+ * dimension -> per-rank slice ranges".
+ *
+ * Readings taken where the paper is silent (all listed in the design notes):
+ *   - weights are 16-bit patterns (bf16); "non-zero delta" means the two bit
+ *     patterns differ (so +0 -> -0 is a change, an identical NaN is not);
+ *   - the payload of an entry is the NEW 16-bit pattern, applying = overwrite
+ *     (an arithmetic bf16 difference is not exact in general, so it could not
+ *     be lossless);
+ *   - an entry's coordinate is one linear index, local to the destination
+ *     shard's copy of that tensor (int32);
+ *   - entries of one (tensor, shard) segment are in ascending local index;
+ *   - a replicated tensor's entries go to every shard.
+ *
+ * Parity pins live in tests/ (numpy flatnonzero for TP=1, numpy slicing for
+ * the shard map, round-trip and counting invariants, torch's CPU cast for
+ * round-to-nearest-even).  No function here is "parity unpinned".
+ */
+#include <stdint.h>
+#include <stddef.h>
+
+/* shard rules (values are part of the tested interface) */
+enum {
+    ORC_REPLICATED = 0, /* every shard holds the whole tensor                */
+    ORC_SPLIT_ROWS = 1, /* dim 0 cut into D equal row blocks                 */
+    ORC_SPLIT_COLS = 2, /* dim 1 cut into D equal column blocks              */
+    ORC_FUSED_ROWS = 3  /* dim 0 is a stack of sections, each cut into D     */
+};
+
+enum { ORC_OK = 0, ORC_BAD_ARG = 1, ORC_BAD_SHAPE = 2, ORC_RANGE = 3, ORC_ORDER = 4 };
+
+/*
+ * fp32 bit pattern -> bf16 bit pattern, round to nearest, ties to even
+ * (IEEE 754 roundTiesToEven applied to the 16 discarded mantissa bits).
+ * NaN stays NaN: keep the top 16 bits and set the quiet bit.
+ */
+uint16_t orc_rne_bf16(uint32_t u)
+{
+    uint32_t mag = u & 0x7FFFFFFFu;
+    if (mag > 0x7F800000u) {
+        return (uint16_t)((u >> 16) | 0x0040u);
+    }
+    uint32_t keep = u >> 16;        /* truncated result                    */
+    uint32_t rest = u & 0xFFFFu;    /* discarded bits, half = 0x8000       */
+    if (rest > 0x8000u) {
+        keep += 1;                  /* above half: up                      */
+    } else if (rest == 0x8000u) {
+        if (keep & 1u) keep += 1;   /* exactly half: to even               */
+    }
+    return (uint16_t)keep;          /* a carry into the exponent is right:
+                                       the largest finite rounds to inf    */
+}
+
+void orc_rne_bf16_array(const uint32_t *in, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_rne_bf16(in[i]);
+}
+
+/* shape checks shared by the functions below */
+static int check_shape(int rule, int64_t R, int64_t C, int n_sec,
+                       const int64_t *sec, int D)
+{
+    if (R < 0 || C < 0 || D < 1) return ORC_BAD_ARG;
+    switch (rule) {
+    case ORC_REPLICATED: return ORC_OK;
+    case ORC_SPLIT_ROWS: return (R % D) ? ORC_BAD_SHAPE : ORC_OK;
+    case ORC_SPLIT_COLS: return (C % D) ? ORC_BAD_SHAPE : ORC_OK;
+    case ORC_FUSED_ROWS: {
+        if (n_sec < 1 || !sec) return ORC_BAD_ARG;
+        int64_t sum = 0;
+        for (int j = 0; j < n_sec; ++j) {
+            if (sec[j] < 0 || sec[j] % D) return ORC_BAD_SHAPE;
+            sum += sec[j];
+        }
+        return (sum == R) ? ORC_OK : ORC_BAD_SHAPE;
+    }
+    default: return ORC_BAD_ARG;
+    }
+}
+
+/* number of elements of shard d's local copy of an (R,C) tensor */
+int64_t orc_local_numel(int rule, int64_t R, int64_t C, int D)
+{
+    if (rule == ORC_REPLICATED) return R * C;
+    return (R * C) / D;
+}
+
+/*
+ * Shard map (Sec. 4.2 "Shard-aware": sharded dimension -> per-rank slice
+ * ranges; textbook tensor-parallel slicing).  Element (r,c) of the full
+ * (R,C) tensor lives on shards d_first .. d_first+n_dest-1 at flat local
+ * index *local (the same on each of them).
+ */
+int orc_shard_map(int rule, int64_t R, int64_t C, int n_sec, const int64_t *sec,
+                  int D, int64_t r, int64_t c,
+                  int *d_first, int *n_dest, int64_t *local)
+{
+    int rc = check_shape(rule, R, C, n_sec, sec, D);
+    if (rc) return rc;
+    if (r < 0 || r >= R || c < 0 || c >= C) return ORC_RANGE;
+
+    if (rule == ORC_REPLICATED) {
+        *d_first = 0; *n_dest = D; *local = r * C + c;
+    } else if (rule == ORC_SPLIT_ROWS) {
+        int64_t rows_per = R / D;
+        int64_t d = r / rows_per;
+        *d_first = (int)d; *n_dest = 1;
+        *local = (r - d * rows_per) * C + c;
+    } else if (rule == ORC_SPLIT_COLS) {
+        int64_t cols_per = C / D;
+        int64_t d = c / cols_per;
+        *d_first = (int)d; *n_dest = 1;
+        *local = r * cols_per + (c - d * cols_per);
+    } else { /* ORC_FUSED_ROWS */
+        int64_t sec_first_row = 0;   /* first full-tensor row of section j  */
+        int64_t loc_first_row = 0;   /* first local row of section j's part */
+        int j = 0;
+        while (r >= sec_first_row + sec[j]) {
+            sec_first_row += sec[j];
+            loc_first_row += sec[j] / D;
+            ++j;
+        }
+        int64_t in_sec = r - sec_first_row;
+        int64_t per = sec[j] / D;
+        int64_t d = in_sec / per;
+        *d_first = (int)d; *n_dest = 1;
+        *local = (loc_first_row + (in_sec - d * per)) * C + c;
+    }
+    return ORC_OK;
+}
+
+/*
+ * Dense-to-sparse for ONE tensor (Sec. 4.2 "Sparsity-aware"; App. F "D2S").
+ *
+ * old_bits : R*C bf16 patterns (W_{t-1})
+ * new_data : R*C bf16 patterns, or R*C fp32 patterns when new_is_f32 != 0
+ *            (then the new weight is first rounded to bf16, ties to even)
+ * counts   : [D] out, number of entries for each shard
+ * idx, val : [D] arrays of caller buffers, or NULL to only count.  When given,
+ *            buffer d must hold counts[d] entries (call once to count first).
+ *
+ * Three plain loops: row, column, destination.  Entries come out in ascending
+ * (r,c); the function checks that this is also ascending local index.
+ */
+int orc_encode_tensor(const uint16_t *old_bits, const void *new_data, int new_is_f32,
+                      int rule, int64_t R, int64_t C, int n_sec, const int64_t *sec,
+                      int D, int64_t *counts, int32_t *const *idx, uint16_t *const *val)
+{
+    int rc = check_shape(rule, R, C, n_sec, sec, D);
+    if (rc) return rc;
+    if (orc_local_numel(rule, R, C, D) > (int64_t)INT32_MAX) return ORC_RANGE;
+    for (int d = 0; d < D; ++d) counts[d] = 0;
+
+    const uint16_t *new16 = (const uint16_t *)new_data;
+    const uint32_t *new32 = (const uint32_t *)new_data;
+
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t c = 0; c < C; ++c) {
+            int64_t g = r * C + c;
+            uint16_t nb = new_is_f32 ? orc_rne_bf16(new32[g]) : new16[g];
+            if (nb == old_bits[g]) continue;            /* zero delta: not sent */
+            int d_first, n_dest; int64_t local;
+            rc = orc_shard_map(rule, R, C, n_sec, sec, D, r, c, &d_first, &n_dest, &local);
+            if (rc) return rc;
+            for (int d = d_first; d < d_first + n_dest; ++d) {
+                int64_t k = counts[d];
+                if (idx) {
+                    if (k > 0 && (int64_t)idx[d][k - 1] >= local) return ORC_ORDER;
+                    idx[d][k] = (int32_t)local;
+                    val[d][k] = nb;
+                }
+                counts[d] = k + 1;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/*
+ * Sparse-to-dense (App. F "S2D"): put each entry's value at its local index
+ * of the receiver's resident copy.  Nothing else is touched.
+ */
+int orc_apply(const int32_t *idx, const uint16_t *val, int64_t count,
+              uint16_t *dst, int64_t dst_numel)
+{
+    for (int64_t k = 0; k < count; ++k) {
+        if (idx[k] < 0 || (int64_t)idx[k] >= dst_numel) return ORC_RANGE;
+        dst[idx[k]] = val[k];
+    }
+    return ORC_OK;
+}
+
+/*
+ * Dense path (Sec. 4.2 "Shard-aware" without sparsity): shard d's local copy
+ * of the full tensor, written out element by element through the shard map.
+ */
+int orc_dense_shard(const uint16_t *full, int rule, int64_t R, int64_t C, int n_sec,
+                    const int64_t *sec, int D, int d, uint16_t *dst)
+{
+    int rc = check_shape(rule, R, C, n_sec, sec, D);
+    if (rc) return rc;
+    if (d < 0 || d >= D) return ORC_RANGE;
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t c = 0; c < C; ++c) {
+            int d_first, n_dest; int64_t local;
+            rc = orc_shard_map(rule, R, C, n_sec, sec, D, r, c, &d_first, &n_dest, &local);
+            if (rc) return rc;
+            if (d >= d_first && d < d_first + n_dest) dst[local] = full[r * C + c];
+        }
+    }
+    return ORC_OK;
+}
