@@ -1,0 +1,178 @@
+/*
+ * rose_delta.h -- C ABI of the MI355X (gfx950) sparse weight-delta library.
+ *
+ * The library implements the data-parallel part of the cross-cluster weight
+ * transfer engine of ROSE (Sec. 4.2): the sender compares the previous and the
+ * updated bf16 parameters, keeps only the changed elements in COO form
+ * ("Sparsity-aware Weight Transfer"; App. F calls the step D2S), already split
+ * by the receiver's tensor-parallel layout ("Shard-aware Weight Transfer":
+ * sharded dimension -> per-rank slice ranges), and every receiver applies its
+ * own part onto its resident previous weights (App. F: S2D).
+ *
+ * Conventions
+ *   - Every pointer is named host or device below.  The library owns only the
+ *     plan handle (and device tables hanging off it); every tensor, bucket,
+ *     pointer table and workspace is caller-owned device memory that must stay
+ *     valid until the work queued on `stream` has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     encode / apply / dense_copy / bw_probe only queue work and return; they do
+ *     not synchronise and do not allocate after the plan's first use on a device.
+ *   - Errors that the host can see are returned before anything is queued.
+ *     No exception crosses this boundary and there is no global state.
+ *   - Weights are 16-bit patterns (bf16).  "Changed" means the two patterns
+ *     differ; an entry carries the new pattern and applying it overwrites.
+ *   - Entry coordinates are int32 flat indices local to the destination shard's
+ *     copy of one tensor; model-wide positions, offsets and counts are int64.
+ */
+#ifndef ROSE_DELTA_H
+#define ROSE_DELTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROSE_MAX_TP 16        /* largest destination tensor-parallel degree */
+#define ROSE_MAX_SECTIONS 4   /* largest number of stacked sections of a fused tensor */
+
+typedef enum {
+    ROSE_OK = 0,
+    ROSE_ERR_ARG = 1,         /* null pointer, index out of range, bad enum value */
+    ROSE_ERR_SHAPE = 2,       /* a sharded dimension is not divisible by tp, sections do not add up */
+    ROSE_ERR_CAPACITY = 3,    /* a bucket was too small (see rose_bucket_check) */
+    ROSE_ERR_ALIGN = 4,       /* a bucket or workspace pointer is not aligned as required */
+    ROSE_ERR_HIP = 5,         /* a HIP runtime call failed (no GPU, launch failure, ...) */
+    ROSE_ERR_UNSUPPORTED = 6  /* a shard-local tensor has 2^31 or more elements, tp > ROSE_MAX_TP */
+} rose_status;
+
+/* How the receiver's layout cuts a row-major (rows, cols) tensor into tp shards. */
+typedef enum {
+    ROSE_REPLICATED = 0,  /* every shard holds the whole tensor (norm weights); its entries go
+                             to every bucket */
+    ROSE_SPLIT_ROWS = 1,  /* dim 0 in tp equal blocks: column-parallel [out,in] matrices, vocabulary */
+    ROSE_SPLIT_COLS = 2,  /* dim 1 in tp equal blocks: row-parallel matrices (o_proj, down_proj) */
+    ROSE_FUSED_ROWS = 3   /* dim 0 is a stack of sections (Q;K;V or gate;up), each cut in tp equal
+                             blocks; shard d holds [sec0_d; sec1_d; ...] */
+} rose_rule;
+
+typedef enum {
+    ROSE_BF16 = 0,        /* the new weights are bf16 patterns */
+    ROSE_FP32_RNE = 1     /* the new weights are fp32 masters, rounded to bf16 (nearest, ties to even,
+                             NaN quieted) inside the kernel before they are compared */
+} rose_src_dtype;
+
+typedef struct {
+    int64_t rows, cols;                            /* full (unsharded) shape; 1-D tensors: rows = 1 */
+    int32_t rule;                                  /* rose_rule */
+    int32_t n_sections;                            /* ROSE_FUSED_ROWS only: 1..ROSE_MAX_SECTIONS */
+    int64_t section_rows[ROSE_MAX_SECTIONS];       /* rows of each section, sum = rows */
+} rose_tensor_desc;
+
+typedef struct rose_plan rose_plan;
+
+/*
+ * One destination shard's COO data (Sec. 4.2 "shard the COO tensors according to the chosen
+ * parallelism strategy").  The struct lives in host memory; all four arrays are device memory.
+ *   idx      [capacity] int32 local indices, 16-byte aligned
+ *   val      [capacity] new 16-bit patterns, 16-byte aligned
+ *   seg_off  [n_tensors + 1] int64, 8-byte aligned: after encode, the entries of tensor t are
+ *            idx/val[seg_off[t] .. seg_off[t+1]), in ascending local index; seg_off[n_tensors]
+ *            is the exact number of entries the shard needs, also when it exceeds capacity
+ *            (then entries at positions >= capacity were dropped, nothing was written out of
+ *            bounds, and the bucket must not be applied).
+ */
+typedef struct {
+    int32_t *idx;
+    uint16_t *val;
+    int64_t capacity;
+    int64_t *seg_off;
+} rose_bucket;
+
+/*
+ * shard_plan (Sec. 4.2 "Shard-aware Weight Transfer"): per tensor, the rule and the per-rank
+ * slice ranges, turned into the tables the kernels walk.  Pure host work, no GPU needed.
+ * `tensors` (host, copied) lists the model's tensors in bucket order.  Errors: ROSE_ERR_ARG,
+ * ROSE_ERR_SHAPE, ROSE_ERR_UNSUPPORTED.  On success *out is a handle to free with
+ * rose_shard_plan_destroy; it is immutable and may be used from several threads.
+ */
+rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
+                                   rose_plan **out);
+void rose_shard_plan_destroy(rose_plan *plan);
+
+/* Host queries on a plan (no GPU needed). */
+int32_t rose_plan_n_tensors(const rose_plan *plan);
+int32_t rose_plan_tp(const rose_plan *plan);
+/* elements of the model before tensor t (int64 model-wide position of its element 0) */
+rose_status rose_plan_tensor_base(const rose_plan *plan, int32_t t, int64_t *global_base);
+/* elements of shard d's local copy of tensor t */
+rose_status rose_plan_local_numel(const rose_plan *plan, int32_t t, int32_t d, int64_t *numel);
+/* flat element g of tensor t lives on shards d_first .. d_first + n_dest - 1 at local index *local */
+rose_status rose_plan_map_index(const rose_plan *plan, int32_t t, int64_t g, int32_t *d_first,
+                                int32_t *n_dest, int32_t *local);
+/* worst-case number of entries of bucket d (every element changed) */
+rose_status rose_plan_bucket_capacity(const rose_plan *plan, int32_t d, int64_t *max_entries);
+/* bytes of device scratch that rose_delta_encode needs (256-byte aligned buffer) */
+rose_status rose_plan_workspace_bytes(const rose_plan *plan, size_t *bytes);
+/* number of tiles the encode kernel walks (for reporting) */
+rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
+
+/*
+ * delta_encode (Sec. 4.2 "Sparsity-aware Weight Transfer", App. F D2S): one pass over the
+ * previous and the new weights that writes all tp buckets.
+ *   old_ptrs, new_ptrs  DEVICE arrays of n_tensors device pointers to the full tensors
+ *                       (row-major; bf16, or fp32 for new when new_dtype = ROSE_FP32_RNE).
+ *                       Tensors aligned to 16 bytes take the 128-bit load path; others still
+ *                       work, more slowly.  Both are only read.
+ *   buckets             HOST array of tp bucket structs; their device arrays are written.
+ *   workspace           DEVICE scratch of at least rose_plan_workspace_bytes, 256-byte aligned;
+ *                       contents before the call do not matter; calls that share a workspace
+ *                       must be ordered on one stream.
+ * Returns ROSE_ERR_ARG / ROSE_ERR_ALIGN / ROSE_ERR_HIP without queuing anything.  A bucket
+ * that is too small is not an error of this call: see rose_bucket_check.
+ */
+rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs,
+                              const void *const *new_ptrs, int32_t new_dtype,
+                              const rose_bucket *buckets, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
+/*
+ * delta_apply (Sec. 4.2 "each device applies only its local shard", App. F S2D): writes every
+ * entry's value at its local index of shard d's resident copies.
+ *   bucket    HOST struct, device arrays as written by rose_delta_encode for shard d
+ *   dst_ptrs  DEVICE array of n_tensors device pointers to shard d's local tensors
+ *             (rose_plan_local_numel elements each, 2-byte aligned at least)
+ * Entries at positions >= capacity (an overflowed bucket) are not applied.
+ */
+rose_status rose_delta_apply(const rose_plan *plan, int32_t d, const rose_bucket *bucket,
+                             void *const *dst_ptrs, void *stream);
+
+/*
+ * Dense path (Sec. 4.2 "Shard-aware Weight Transfer" without sparsity; the comparison the
+ * Sec. 6.3 crossover is measured against): dst = shard d's slice of the new weights.
+ * Pointer tables as above.
+ */
+rose_status rose_dense_copy(const rose_plan *plan, int32_t d, const void *const *new_ptrs,
+                            int32_t new_dtype, void *const *dst_ptrs, void *stream);
+
+/*
+ * Synchronises `stream`, reads seg_off[n_tensors] of the bucket back and returns
+ * ROSE_ERR_CAPACITY if it exceeds capacity.  *required (host, may be NULL) gets the count.
+ */
+rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, void *stream,
+                              int64_t *required);
+
+/*
+ * Bandwidth probe, for measuring what HBM delivers beside the kernels above: copies `bytes`
+ * (a multiple of 16) from src to dst (device, 16-byte aligned); with dst = NULL it only reads
+ * src and adds a checksum into *sink (device, 8 bytes, required in that mode).
+ */
+rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
+
+const char *rose_status_str(rose_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROSE_DELTA_H */

@@ -1,0 +1,203 @@
+"""Thin ctypes binding of librose_delta.so (declared in include/rose_delta.h).
+
+Argument marshalling only: every step of the path (diff, compaction, shard routing, apply)
+runs in the library's HIP kernels.  torch tensors are used as device memory; this module reads
+their ``data_ptr()`` and the current HIP stream, nothing else.  There is no fallback: if the
+library has not been built, importing this module fails.
+"""
+import ctypes
+import os
+
+import torch
+
+ROSE_MAX_TP = 16
+ROSE_MAX_SECTIONS = 4
+REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
+BF16, FP32_RNE = 0, 1
+OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED = range(7)
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librose_delta.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError("librose_delta.so is not built: run `python -m paper_2605_06534_amd.build` "
+                      "(there is no CPU fallback)")
+_lib = ctypes.CDLL(_LIB_PATH)
+
+
+class TensorDesc(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("rule", ctypes.c_int32),
+                ("n_sections", ctypes.c_int32), ("section_rows", ctypes.c_int64 * ROSE_MAX_SECTIONS)]
+
+
+class CBucket(ctypes.Structure):
+    _fields_ = [("idx", ctypes.c_void_p), ("val", ctypes.c_void_p), ("capacity", ctypes.c_int64),
+                ("seg_off", ctypes.c_void_p)]
+
+
+_vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+_P = ctypes.POINTER
+_SIGS = {
+    "rose_shard_plan_create": (_i32, [_P(TensorDesc), _i32, _i32, _P(_vp)]),
+    "rose_shard_plan_destroy": (None, [_vp]),
+    "rose_plan_n_tensors": (_i32, [_vp]),
+    "rose_plan_tp": (_i32, [_vp]),
+    "rose_plan_tensor_base": (_i32, [_vp, _i32, _P(_i64)]),
+    "rose_plan_local_numel": (_i32, [_vp, _i32, _i32, _P(_i64)]),
+    "rose_plan_map_index": (_i32, [_vp, _i32, _i64, _P(_i32), _P(_i32), _P(_i32)]),
+    "rose_plan_bucket_capacity": (_i32, [_vp, _i32, _P(_i64)]),
+    "rose_plan_workspace_bytes": (_i32, [_vp, _P(ctypes.c_size_t)]),
+    "rose_plan_n_tiles": (_i32, [_vp, _P(_i64)]),
+    "rose_delta_encode": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
+    "rose_delta_apply": (_i32, [_vp, _i32, _P(CBucket), _vp, _vp]),
+    "rose_dense_copy": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp]),
+    "rose_bucket_check": (_i32, [_vp, _P(CBucket), _vp, _P(_i64)]),
+    "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
+    "rose_status_str": (ctypes.c_char_p, [_i32]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(_lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+EXPORTS = tuple(_SIGS)
+
+
+class RoseError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s: %s" % (what, _lib.rose_status_str(status).decode()))
+
+
+def _check(status, what):
+    if status != OK:
+        raise RoseError(status, what)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+class Plan:
+    """Handle of a shard plan (rose_shard_plan_create)."""
+
+    def __init__(self, handle, tensors):
+        self._h = handle
+        self.tensors = tensors
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            _lib.rose_shard_plan_destroy(self._h)
+            self._h = None
+
+    @property
+    def n_tensors(self):
+        return _lib.rose_plan_n_tensors(self._h)
+
+    @property
+    def tp(self):
+        return _lib.rose_plan_tp(self._h)
+
+    def tensor_base(self, t):
+        v = _i64()
+        _check(_lib.rose_plan_tensor_base(self._h, t, ctypes.byref(v)), "plan_tensor_base")
+        return v.value
+
+    def local_numel(self, t, d):
+        v = _i64()
+        _check(_lib.rose_plan_local_numel(self._h, t, d, ctypes.byref(v)), "plan_local_numel")
+        return v.value
+
+    def map_index(self, t, g):
+        a, b, c = _i32(), _i32(), _i32()
+        _check(_lib.rose_plan_map_index(self._h, t, g, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
+               "plan_map_index")
+        return a.value, b.value, c.value
+
+    def bucket_capacity(self, d):
+        v = _i64()
+        _check(_lib.rose_plan_bucket_capacity(self._h, d, ctypes.byref(v)), "plan_bucket_capacity")
+        return v.value
+
+    def workspace_bytes(self):
+        v = ctypes.c_size_t()
+        _check(_lib.rose_plan_workspace_bytes(self._h, ctypes.byref(v)), "plan_workspace_bytes")
+        return v.value
+
+    def n_tiles(self):
+        v = _i64()
+        _check(_lib.rose_plan_n_tiles(self._h, ctypes.byref(v)), "plan_n_tiles")
+        return v.value
+
+
+def shard_plan(tensors, tp):
+    """tensors: list of dicts with rows, cols, rule and (fused rows) sections."""
+    arr = (TensorDesc * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i].rows, arr[i].cols, arr[i].rule = t["rows"], t["cols"], t["rule"]
+        sec = t.get("sections") or []
+        if len(sec) > ROSE_MAX_SECTIONS:
+            raise RoseError(ERR_ARG, "shard_plan")
+        arr[i].n_sections = len(sec)
+        for j, s in enumerate(sec):
+            arr[i].section_rows[j] = s
+    h = _vp()
+    _check(_lib.rose_shard_plan_create(arr, len(tensors), tp, ctypes.byref(h)), "shard_plan")
+    return Plan(h, list(tensors))
+
+
+class Bucket:
+    """Device arrays of one destination shard's COO data (caller-owned torch tensors)."""
+
+    def __init__(self, capacity, n_tensors, device="cuda"):
+        self.capacity = int(capacity)
+        self.idx = torch.empty(max(self.capacity, 4), dtype=torch.int32, device=device)
+        self.val = torch.empty(max(self.capacity, 8), dtype=torch.int16, device=device)
+        self.seg_off = torch.zeros(n_tensors + 1, dtype=torch.int64, device=device)
+
+    def c(self):
+        return CBucket(self.idx.data_ptr(), self.val.data_ptr(), self.capacity, self.seg_off.data_ptr())
+
+
+def ptr_table(tensors, device="cuda"):
+    """Device array of the tensors' device pointers (keep the tensors alive yourself)."""
+    return torch.tensor([t.data_ptr() for t in tensors], dtype=torch.int64, device=device)
+
+
+def workspace(plan, device="cuda"):
+    return torch.empty((plan.workspace_bytes() + 7) // 8, dtype=torch.int64, device=device)
+
+
+def delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=None):
+    cb = (CBucket * plan.tp)(*[b.c() for b in buckets])
+    _check(_lib.rose_delta_encode(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, cb,
+                                  ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
+           "delta_encode")
+
+
+def delta_apply(plan, d, bucket, dst_tab, stream=None):
+    cb = bucket.c()
+    _check(_lib.rose_delta_apply(plan._h, d, ctypes.byref(cb), dst_tab.data_ptr(), _stream(stream)),
+           "delta_apply")
+
+
+def dense_copy(plan, d, new_tab, new_dtype, dst_tab, stream=None):
+    _check(_lib.rose_dense_copy(plan._h, d, new_tab.data_ptr(), new_dtype, dst_tab.data_ptr(),
+                                _stream(stream)), "dense_copy")
+
+
+def bucket_check(plan, bucket, stream=None):
+    """-> number of entries the bucket needs; raises RoseError(ERR_CAPACITY) if it overflowed."""
+    cb, req = bucket.c(), _i64()
+    st = _lib.rose_bucket_check(plan._h, ctypes.byref(cb), _stream(stream), ctypes.byref(req))
+    if st == ERR_CAPACITY:
+        e = RoseError(st, "bucket_check")
+        e.required = req.value
+        raise e
+    _check(st, "bucket_check")
+    return req.value
+
+
+def bw_probe(src, dst=None, sink=None, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(_lib.rose_bw_probe(src.data_ptr(), dst.data_ptr() if dst is not None else None, nbytes,
+                              sink.data_ptr() if sink is not None else None, _stream(stream)), "bw_probe")

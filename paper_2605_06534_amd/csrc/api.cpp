@@ -1,0 +1,135 @@
+// C ABI: argument checks, the plan's device tables, and hand-off to the kernel launchers.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+
+#include "rose_internal.h"
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Copy the piece and tile tables to the current device once; later calls on the same device
+// reuse them.  A plan is bound to the first device it is used on.
+rose_status device_tables(const rose_plan *p, const rose::Piece **pieces, const int32_t **tile_piece) {
+    std::lock_guard<std::mutex> lock(p->mu);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return ROSE_ERR_HIP;
+    if (p->device == -1) {
+        rose::Piece *dp = nullptr;
+        int32_t *dt = nullptr;
+        size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
+        if (hipMalloc(reinterpret_cast<void **>(&dp), pb) != hipSuccess) return ROSE_ERR_HIP;
+        if (hipMalloc(reinterpret_cast<void **>(&dt), tb) != hipSuccess) {
+            (void)hipFree(dp);
+            return ROSE_ERR_HIP;
+        }
+        if (hipMemcpy(dp, p->pieces.data(), pb, hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(dt, p->tile_piece.data(), tb, hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(dp);
+            (void)hipFree(dt);
+            return ROSE_ERR_HIP;
+        }
+        p->d_pieces = dp;
+        p->d_tile_piece = dt;
+        p->device = dev;
+    } else if (p->device != dev) {
+        return ROSE_ERR_ARG;
+    }
+    *pieces = p->d_pieces;
+    *tile_piece = p->d_tile_piece;
+    return ROSE_OK;
+}
+
+rose_status check_bucket(const rose_bucket &b) {
+    if (b.capacity < 0 || !b.seg_off) return ROSE_ERR_ARG;
+    if (b.capacity > 0 && (!b.idx || !b.val)) return ROSE_ERR_ARG;
+    if (!aligned(b.idx, 16) || !aligned(b.val, 16) || !aligned(b.seg_off, 8)) return ROSE_ERR_ALIGN;
+    return ROSE_OK;
+}
+
+}  // namespace
+
+extern "C" void rose_shard_plan_destroy(rose_plan *p) {
+    if (!p) return;
+    if (p->d_pieces) (void)hipFree(p->d_pieces);
+    if (p->d_tile_piece) (void)hipFree(p->d_tile_piece);
+    delete p;
+}
+
+extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *old_ptrs,
+                                         const void *const *new_ptrs, int32_t new_dtype,
+                                         const rose_bucket *buckets, void *workspace,
+                                         size_t workspace_bytes, void *stream) {
+    if (!p || !old_ptrs || !new_ptrs || !buckets || !workspace) return ROSE_ERR_ARG;
+    if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
+    size_t need = 0;
+    rose_plan_workspace_bytes(p, &need);
+    if (workspace_bytes < need) return ROSE_ERR_ARG;
+    if (!aligned(workspace, 256) || !aligned(old_ptrs, 8) || !aligned(new_ptrs, 8)) return ROSE_ERR_ALIGN;
+    rose::EncodeArgs a;
+    std::memset(&a, 0, sizeof a);
+    for (int32_t d = 0; d < p->tp; ++d) {
+        rose_status s = check_bucket(buckets[d]);
+        if (s != ROSE_OK) return s;
+        a.bucket[d].idx = buckets[d].idx;
+        a.bucket[d].val = buckets[d].val;
+        a.bucket[d].capacity = buckets[d].capacity;
+        a.bucket[d].seg_off = buckets[d].seg_off;
+    }
+    std::memcpy(a.chain_first, p->chain_first, sizeof a.chain_first);
+    rose_status s = device_tables(p, &a.pieces, &a.tile_piece);
+    if (s != ROSE_OK) return s;
+    a.old_ptrs = old_ptrs;
+    a.new_ptrs = new_ptrs;
+    a.ticket = static_cast<unsigned int *>(workspace);
+    a.desc = reinterpret_cast<unsigned long long *>(static_cast<char *>(workspace) + 256);
+    a.n_tiles = (int32_t)p->tile_piece.size();
+    a.n_tensors = p->n_tensors;
+    return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const rose_bucket *bucket,
+                                        void *const *dst_ptrs, void *stream) {
+    if (!p || !bucket || !dst_ptrs || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
+    rose_status s = check_bucket(*bucket);
+    if (s != ROSE_OK) return s;
+    if (!aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
+    rose::BucketDev b{bucket->idx, bucket->val, bucket->capacity, bucket->seg_off};
+    return rose::launch_apply(b, p->n_tensors, dst_ptrs, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_dense_copy(const rose_plan *p, int32_t d, const void *const *new_ptrs,
+                                       int32_t new_dtype, void *const *dst_ptrs, void *stream) {
+    if (!p || !new_ptrs || !dst_ptrs || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
+    if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
+    if (!aligned(new_ptrs, 8) || !aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
+    rose::CopyArgs a;
+    std::memset(&a, 0, sizeof a);
+    rose_status s = device_tables(p, &a.pieces, &a.tile_piece);
+    if (s != ROSE_OK) return s;
+    a.new_ptrs = new_ptrs;
+    a.dst_ptrs = dst_ptrs;
+    a.tile_begin = p->chain_first[d];
+    a.n_tiles = p->chain_first[d + 1] - p->chain_first[d];
+    return rose::launch_dense_copy(a, new_dtype == ROSE_FP32_RNE, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_bucket_check(const rose_plan *p, const rose_bucket *bucket, void *stream,
+                                         int64_t *required) {
+    if (!p || !bucket || !bucket->seg_off) return ROSE_ERR_ARG;
+    int64_t total = 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(&total, bucket->seg_off + p->n_tensors, sizeof total, hipMemcpyDeviceToHost, st) != hipSuccess)
+        return ROSE_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return ROSE_ERR_HIP;
+    if (required) *required = total;
+    return total > bucket->capacity ? ROSE_ERR_CAPACITY : ROSE_OK;
+}
+
+extern "C" rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream) {
+    if (!src || (bytes & 15u)) return ROSE_ERR_ARG;
+    if (!dst && !sink) return ROSE_ERR_ARG;
+    if (!aligned(src, 16) || !aligned(dst, 16) || !aligned(sink, 8)) return ROSE_ERR_ALIGN;
+    return rose::launch_bw_probe(src, dst, bytes, sink, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+}

@@ -1,0 +1,108 @@
+// Internal declarations shared by the host planner, the C ABI and the kernel launchers.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "rose_delta.h"
+
+namespace rose {
+
+// Tile geometry of the encode / dense-copy kernels: one workgroup of kThreads lanes walks one
+// tile; a lane takes kIters vectors of kVec 16-bit elements (one 128-bit load each).
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kVec = 8;
+#ifndef ROSE_ITERS
+#define ROSE_ITERS 4
+#endif
+constexpr int kIters = ROSE_ITERS;
+constexpr int kWaveSpan = 64 * kVec * kIters;      // elements one wave covers in a tile
+constexpr int kTile = kThreads * kVec * kIters;    // elements per tile
+
+enum : int32_t {
+    kPieceFirst = 1,    // first piece of its (tensor, shard) segment
+    kPieceVec = 2,      // offsets and run lengths are multiples of kVec: 128-bit loads are legal
+    kPieceStrided = 4   // runs of `run` elements every `stride` source elements
+};
+
+// One run of a (tensor, shard) segment's local index space that maps to the source tensor
+// either contiguously or as equal runs at a fixed stride (a column block of a row-parallel
+// matrix).  Local index local_base + k  <->  source element
+//   src_off + k                                    (contiguous)
+//   src_off + (k / run) * stride + k % run         (strided)
+struct Piece {
+    int64_t src_off;
+    int64_t stride;
+    int32_t tensor;
+    int32_t shard;
+    int32_t local_base;
+    int32_t len;
+    int32_t run;
+    uint32_t magic;      // k / run == mulhi(k, magic) >> shift for k < 2^31 (run >= 2)
+    uint32_t shift;
+    int32_t first_tile;
+    int32_t flags;
+    int32_t pad;
+};
+static_assert(sizeof(Piece) == 56, "Piece layout is shared with device code");
+
+struct BucketDev {
+    int32_t *idx;
+    uint16_t *val;
+    int64_t capacity;
+    int64_t *seg_off;
+};
+
+struct EncodeArgs {
+    BucketDev bucket[ROSE_MAX_TP];
+    int32_t chain_first[ROSE_MAX_TP + 1];   // first tile of each shard's chain; [tp] = n_tiles
+    const Piece *pieces;
+    const int32_t *tile_piece;
+    const void *const *old_ptrs;
+    const void *const *new_ptrs;
+    unsigned long long *desc;               // one look-back descriptor per tile
+    unsigned int *ticket;
+    int32_t n_tiles;
+    int32_t n_tensors;
+};
+
+struct CopyArgs {
+    const Piece *pieces;
+    const int32_t *tile_piece;
+    const void *const *new_ptrs;
+    void *const *dst_ptrs;
+    int32_t tile_begin;
+    int32_t n_tiles;
+};
+
+// host side of the magic-number division used for strided pieces
+void make_magic(uint32_t divisor, uint32_t *magic, uint32_t *shift);
+inline uint32_t magic_div(uint32_t k, uint32_t magic, uint32_t shift) {
+    return (uint32_t)(((uint64_t)k * magic) >> 32) >> shift;
+}
+
+// kernel launchers (kernels.hip); all return a hipError_t as int
+int launch_encode(const EncodeArgs &a, int new_is_f32, void *stream);
+int launch_apply(const BucketDev &b, int32_t n_tensors, void *const *dst_ptrs, void *stream);
+int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
+int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
+
+}  // namespace rose
+
+struct rose_plan {
+    int32_t tp = 0;
+    int32_t n_tensors = 0;
+    std::vector<rose_tensor_desc> tensors;
+    std::vector<int64_t> global_base;          // [n_tensors + 1]
+    std::vector<rose::Piece> pieces;
+    std::vector<int32_t> tile_piece;           // piece of each tile
+    int32_t chain_first[ROSE_MAX_TP + 1] = {0};
+    // device copies of pieces / tile_piece, made on first use on a device
+    mutable std::mutex mu;
+    mutable int device = -1;
+    mutable rose::Piece *d_pieces = nullptr;
+    mutable int32_t *d_tile_piece = nullptr;
+};

@@ -1,0 +1,105 @@
+"""Host-side checks of the C-ABI library that need no GPU: every declared symbol is exported,
+the planner's tables agree with the oracle's shard map, argument errors are reported."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_06534_amd as R
+from paper_2605_06534_amd import binding
+from oracle import oracle
+from workloads import models
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "rose_delta.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rose_[a-z0-9_]+)\s*\(", header))
+    assert {"rose_shard_plan_create", "rose_delta_encode", "rose_delta_apply"} <= declared
+    lib = ctypes.CDLL(binding._LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+SHAPES = [
+    (R.REPLICATED, 1, 40, None), (R.REPLICATED, 3, 5, None),
+    (R.SPLIT_ROWS, 16, 3, None), (R.SPLIT_ROWS, 8, 16, None),
+    (R.SPLIT_COLS, 3, 16, None), (R.SPLIT_COLS, 5, 64, None), (R.SPLIT_COLS, 1, 32, None),
+    (R.SPLIT_COLS, 7, 8, None),
+    (R.FUSED_ROWS, 32, 8, [16, 8, 8]), (R.FUSED_ROWS, 24, 3, [8, 0, 16]), (R.FUSED_ROWS, 8, 4, [8]),
+]
+
+
+@pytest.mark.parametrize("tp", [1, 2, 4, 8])
+def test_planner_tables_match_oracle_map(tp):
+    ts = [dict(name="t%d" % i, rows=r, cols=c, rule=rule, sections=sec)
+          for i, (rule, r, c, sec) in enumerate(SHAPES)]
+    plan = R.shard_plan(ts, tp)
+    assert plan.n_tensors == len(ts) and plan.tp == tp
+    base = 0
+    for i, t in enumerate(ts):
+        assert plan.tensor_base(i) == base
+        base += t["rows"] * t["cols"]
+        for d in range(tp):
+            assert plan.local_numel(i, d) == oracle.local_numel(t["rule"], t["rows"], t["cols"], tp)
+        for g in range(t["rows"] * t["cols"]):
+            want = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], tp,
+                                    g // t["cols"], g % t["cols"])
+            assert plan.map_index(i, g) == want, (i, g)
+    assert plan.tensor_base(len(ts)) == base
+    assert plan.bucket_capacity(0) == sum(plan.local_numel(i, 0) for i in range(len(ts)))
+    assert plan.workspace_bytes() == 256 + 8 * plan.n_tiles()
+
+
+def test_large_shapes_sampled_against_oracle():
+    ts = models.decoder(1, 5120, 40, 8, 128, 27648, 152064)
+    plan = R.shard_plan(ts, 8)
+    import random
+    rnd = random.Random(0)
+    for i, t in enumerate(ts):
+        n = t["rows"] * t["cols"]
+        for g in [0, n - 1] + [rnd.randrange(n) for _ in range(20)]:
+            want = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], 8,
+                                    g // t["cols"], g % t["cols"])
+            assert plan.map_index(i, g) == want
+
+
+def test_argument_errors():
+    def plan(rows, cols, rule, tp, sections=None):
+        return R.shard_plan([dict(rows=rows, cols=cols, rule=rule, sections=sections)], tp)
+
+    for args, status in [
+        ((6, 4, R.SPLIT_ROWS, 4), binding.ERR_SHAPE),
+        ((4, 6, R.SPLIT_COLS, 4), binding.ERR_SHAPE),
+        ((12, 4, R.FUSED_ROWS, 4, [8, 2, 2]), binding.ERR_SHAPE),
+        ((12, 4, R.FUSED_ROWS, 4, [8, 8]), binding.ERR_SHAPE),
+        ((12, 4, R.FUSED_ROWS, 4), binding.ERR_ARG),            # no sections
+        ((4, 4, 7, 2), binding.ERR_ARG),                        # unknown rule
+        ((-1, 4, R.SPLIT_ROWS, 1), binding.ERR_ARG),
+        ((4, 4, R.SPLIT_ROWS, 0), binding.ERR_ARG),
+        ((32, 4, R.SPLIT_ROWS, 32), binding.ERR_UNSUPPORTED),   # tp above ROSE_MAX_TP
+        ((1, 1 << 31, R.REPLICATED, 1), binding.ERR_UNSUPPORTED),   # local numel >= 2^31
+        ((1 << 20, 1 << 45, R.REPLICATED, 1), binding.ERR_UNSUPPORTED),
+    ]:
+        with pytest.raises(R.RoseError) as e:
+            plan(*args)
+        assert e.value.status == status, args
+    with pytest.raises(R.RoseError):
+        R.shard_plan([], 1)
+    p = plan(8, 8, R.SPLIT_ROWS, 2)
+    for bad in (lambda: p.local_numel(1, 0), lambda: p.local_numel(0, 2), lambda: p.map_index(0, 64),
+                lambda: p.bucket_capacity(-1), lambda: p.tensor_base(2)):
+        with pytest.raises(R.RoseError):
+            bad()
+    # a 2^31 - 8 element flat tensor at TP = 1 is the largest accepted local size class
+    assert plan(1, (1 << 31) - 8, R.REPLICATED, 1).local_numel(0, 0) == (1 << 31) - 8
+
+
+def test_empty_tensor_gets_a_tile():
+    p = R.shard_plan([dict(rows=0, cols=8, rule=R.SPLIT_ROWS, sections=None),
+                      dict(rows=4, cols=8, rule=R.SPLIT_ROWS, sections=None)], 2)
+    assert p.n_tiles() == 4 and p.local_numel(0, 1) == 0
