@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse weight-delta hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic parameter-set update: delta_encode of
+all tensors into every destination bucket, then delta_apply of every bucket into the receiver's
+shard copies.  Default workload: the 7B-style decoder re-sharded to TP = 4 at 5 % change density.
+Prints one JSON line (metric: dense GB/s scanned = 4 bytes per element / step time).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="decoder7b_tp4",
+                    choices=["matrix4096_tp1", "decoder7b_tp4", "flat1g_tp1", "decoder32b_tp8", "decoder32b_tp8_f32"])
+    ap.add_argument("--density", type=float, default=None, help="change density p (default: the workload's)")
+    ap.add_argument("--layers", type=int, default=None, help="fewer decoder layers (debugging only)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=float, default=2.0e9)
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per encode launch from rocprofv3 counters, to report as roofline.traffic")
+    return ap.parse_args()
+
+
+def workload(args):
+    from workloads import models
+    w = args.workload
+    if w == "matrix4096_tp1":
+        return models.single_matrix(), 1, "bernoulli", 0.01
+    if w == "decoder7b_tp4":
+        return models.decoder_7b(args.layers or 32), 4, "bernoulli", 0.05
+    if w == "flat1g_tp1":
+        return models.flat(1 << 30), 1, "bernoulli", 0.01
+    if w == "decoder32b_tp8":
+        return models.decoder_32b(args.layers or 64), 8, "bernoulli", 0.02
+    return models.decoder_32b(args.layers or 64), 8, "clustered_f32", None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (all destination buckets are produced and applied "
+              "on the one device; there are no collectives). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+
+    import paper_2605_06534_amd as R
+    from workloads import models, synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tensors, tp, recipe, p = workload(args)
+    if args.density is not None:
+        p = args.density
+    n_elems = models.numel(tensors)
+
+    # ---- inputs resident in HBM: W_{t-1}, W_t, the receiver's shard copies, buckets ----
+    olds, news = [], []
+    kw = {"p": p} if recipe == "bernoulli" else {"vocab_active": 20000}
+    for _, _, o, n in synth.model_pairs(tensors, recipe, args.seed, "cuda", **kw):
+        olds.append(o)
+        news.append(n)
+    new_dtype = R.FP32_RNE if recipe == "clustered_f32" else R.BF16
+    plan = R.shard_plan(tensors, tp)
+    old_tab, new_tab = R.ptr_table(olds), R.ptr_table(news)
+    ws = R.workspace(plan)
+    frac = 0.06 if p is None else min(1.0, 1.3 * p + 0.002)
+    buckets = [R.Bucket(int(plan.bucket_capacity(d) * frac) + 4096, len(tensors)) for d in range(tp)]
+    shards, shard_tabs = [], []
+    for d in range(tp):
+        loc = [torch.empty(plan.local_numel(t, d), dtype=torch.bfloat16, device=dev) for t in range(len(tensors))]
+        tab = R.ptr_table(loc)
+        R.dense_copy(plan, d, old_tab, R.BF16, tab)        # receiver starts from W_{t-1}
+        shards.append(loc)
+        shard_tabs.append(tab)
+    torch.cuda.synchronize()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
+        if ev:
+            ev[1].record()
+        for d in range(tp):
+            R.delta_apply(plan, d, buckets[d], shard_tabs[d])
+        if ev:
+            ev[2].record()
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    nnz = [R.bucket_check(plan, buckets[d]) for d in range(tp)]    # raises if a bucket overflowed
+    nnz_total = sum(nnz)
+
+    # the receiver now holds W_t: check one shard tensor per rule class against a dense copy
+    chk = [torch.empty_like(x) for x in shards[tp - 1]]
+    R.dense_copy(plan, tp - 1, new_tab, new_dtype, R.ptr_table(chk))
+    torch.cuda.synchronize()
+    for a, b in zip(shards[tp - 1], chk):
+        if not torch.equal(a.view(torch.int16), b.view(torch.int16)):
+            print("bench.py: applied shard differs from the dense copy of the new weights", file=sys.stderr)
+            sys.exit(1)
+    del chk
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    t_enc = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps      # ms, HIP events on the launch stream
+    t_app = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+
+    in_bytes_per_elem = 6 if new_dtype == R.FP32_RNE else 4
+    scanned = in_bytes_per_elem * n_elems
+    enc_bytes = scanned + 6 * nnz_total            # algorithmic: read old + new once, write idx + val
+    app_bytes = 8 * nnz_total                      # read idx + val, write val
+    value = scanned / 1e9 / (ms_per_step / 1e3)
+
+    # ---- bandwidth probe in the same run (1 GiB buffers) ----
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, dtype=torch.int64, device=dev)
+    probe = {}
+    for name, d_, s_ in (("copy", dst, None), ("read", None, sink)):
+        for _ in range(2):
+            R.bw_probe(src, d_, s_)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            R.bw_probe(src, d_, s_)
+        b.record()
+        torch.cuda.synchronize()
+        moved = (2 if name == "copy" else 1) * src.numel() * 10
+        probe[name + "_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
+    del src, dst
+
+    out = {
+        "metric": "weight-delta encode+apply GB/s (bf16 scanned)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u16", "data": "synthetic",
+        "config": {"workload": args.workload, "elements": n_elems, "tensors": len(tensors), "tp": tp,
+                   "recipe": recipe, "density": p, "nnz": nnz_total, "seed": args.seed,
+                   "new_dtype": "fp32->bf16 RNE" if new_dtype == R.FP32_RNE else "bf16"},
+        "roofline": {"bound": "hbm", "kernel": "encode_kernel",
+                     "achieved": round(enc_bytes / 1e9 / (t_enc / 1e3), 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(enc_bytes / 1e9 / (t_enc / 1e3) / HBM_PEAK_GBS, 4),
+                     "traffic": args.traffic_bytes,
+                     "algorithmic_bytes": enc_bytes, "launch_ms": round(t_enc, 4)},
+        "detail": {"t_encode_ms": round(t_enc, 4), "t_apply_ms": round(t_app, 4),
+                   "encode_scanned_GBs": round(scanned / 1e9 / (t_enc / 1e3), 1),
+                   "apply_algorithmic_GBs": round(app_bytes / 1e9 / (t_app / 1e3), 1) if t_app > 0 else None,
+                   "encode_plus_apply_algorithmic_frac_of_peak":
+                       round((enc_bytes + app_bytes) / 1e9 / ((t_enc + t_app) / 1e3) / HBM_PEAK_GBS, 4),
+                   "bw_probe": probe, "tiles": plan.n_tiles()},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(tensors, tp, olds, news, args.cpu_sample_elems, in_bytes_per_elem)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(tensors, tp, olds, news, sample_elems, in_bytes_per_elem):
+    """The oracle as it stands, one thread, on the first tensors of the same workload (streamed
+    from the device one tensor at a time; copies are not timed)."""
+    import numpy as np
+    from oracle import oracle
+
+    def host(t):
+        t = t.detach().cpu().contiguous()
+        if t.dtype == torch.float32:
+            return t.view(torch.int32).numpy().view(np.uint32)
+        return t.view(torch.int16).numpy().view(np.uint16)
+
+    done, secs, names = 0, 0.0, 0
+    for t, o, n in zip(tensors, olds, news):
+        if done >= sample_elems:
+            break
+        ho, hn = host(o), host(n)
+        dsts = [np.zeros(oracle.local_numel(t["rule"], t["rows"], t["cols"], tp), dtype=np.uint16) for _ in range(tp)]
+        t0 = time.perf_counter()
+        segs = oracle.encode_tensor(ho, hn, t["rows"], t["cols"], t["rule"], t["sections"], tp)
+        for d, (idx, val) in enumerate(segs):
+            oracle.apply_segment(idx, val, dsts[d])
+        secs += time.perf_counter() - t0
+        done += ho.size
+        names += 1
+    return {"value": round(in_bytes_per_elem * done / 1e9 / secs, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d tensors of the workload (%d elements), encode+apply, %.1f s" % (names, done, secs)}
+
+
+if __name__ == "__main__":
+    main()

@@ -64,11 +64,14 @@ def test_ragged_flat_sizes(numel):
 def test_odd_shapes_take_the_element_path():
     """Columns and row pieces that are not multiples of 8 elements."""
     print("case: odd shapes", flush=True)
-    ts = [T(33, 5, R.SPLIT_ROWS), T(7, 12, R.SPLIT_COLS), T(129, 36, R.SPLIT_COLS),
+    ts = [T(34, 5, R.SPLIT_ROWS), T(7, 12, R.SPLIT_COLS), T(129, 36, R.SPLIT_COLS),
           T(24, 3, R.FUSED_ROWS, [12, 6, 6]), T(6, 2, R.SPLIT_COLS), T(3, 1000, R.SPLIT_COLS),
           T(0, 16, R.SPLIT_ROWS), T(2, 20000, R.SPLIT_COLS)]
     full_parity(bern_case(ts, 2, 0.2, seed=3))
-    full_parity(bern_case(ts[:3] + ts[5:7], 3, 0.2, seed=5))
+    ts3 = [T(33, 5, R.SPLIT_ROWS), T(7, 12, R.SPLIT_COLS), T(129, 36, R.SPLIT_COLS),
+           T(5, 3, R.SPLIT_COLS), T(0, 16, R.SPLIT_ROWS), T(4, 30000, R.SPLIT_COLS),
+           T(27, 7, R.FUSED_ROWS, [9, 18])]
+    full_parity(bern_case(ts3, 3, 0.2, seed=5))
 
 
 def test_single_changes_and_special_patterns():
