@@ -43,7 +43,7 @@ typedef enum {
     ROSE_ERR_SHAPE = 2,       /* a sharded dimension is not divisible by tp, sections do not add up */
     ROSE_ERR_CAPACITY = 3,    /* a bucket was too small (see rose_bucket_check) */
     ROSE_ERR_ALIGN = 4,       /* a bucket or workspace pointer is not aligned as required */
-    ROSE_ERR_HIP = 5,         /* a HIP runtime call failed (no GPU, launch failure, ...) */
+    ROSE_ERR_HIP = 5,         /* a HIP runtime call failed (no GPU, launch failure), or an encode launch gave up */
     ROSE_ERR_UNSUPPORTED = 6  /* a shard-local tensor has 2^31 or more elements, tp > ROSE_MAX_TP */
 } rose_status;
 
@@ -131,6 +131,11 @@ rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
  *                       must be ordered on one stream.
  * Returns ROSE_ERR_ARG / ROSE_ERR_ALIGN / ROSE_ERR_HIP without queuing anything.  A bucket
  * that is too small is not an error of this call: see rose_bucket_check.
+ *
+ * The kernel's workgroups wait on each other's tile counts.  The wait is bounded: if a count does
+ * not arrive within a few seconds the launch is marked as failed, every workgroup still exits,
+ * seg_off[n_tensors] of every bucket is set to -1, rose_bucket_check returns ROSE_ERR_HIP and
+ * rose_delta_apply of such a bucket does nothing.
  */
 rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs,
                               const void *const *new_ptrs, int32_t new_dtype,
@@ -166,7 +171,8 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
 /*
  * Bandwidth probe, for measuring what HBM delivers beside the kernels above: copies `bytes`
  * (a multiple of 16) from src to dst (device, 16-byte aligned); with dst = NULL it only reads
- * src and adds a checksum into *sink (device, 8 bytes, required in that mode).
+ * src; *sink (device, 8 bytes, required in that mode) exists so that the reads cannot be dropped
+ * and is incremented for the rare lane whose checksum hits a fixed constant.
  */
 rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
 

@@ -16,11 +16,11 @@ REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
 BF16, FP32_RNE = 0, 1
 OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED = range(7)
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librose_delta.so")
+_LIB_PATH = os.environ.get("ROSE_DELTA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                            "librose_delta.so")
 if not os.path.exists(_LIB_PATH):
-    raise ImportError("librose_delta.so is not built: run `python -m paper_2605_06534_amd.build` "
-                      "(there is no CPU fallback)")
-_lib = ctypes.CDLL(_LIB_PATH)
+    raise ImportError("%s is not built: run `python -m paper_2605_06534_amd.build` "
+                      "(there is no CPU fallback)" % _LIB_PATH)
 
 
 class TensorDesc(ctypes.Structure):
@@ -53,9 +53,17 @@ _SIGS = {
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
     "rose_status_str": (ctypes.c_char_p, [_i32]),
 }
-for _name, (_res, _args) in _SIGS.items():
-    _f = getattr(_lib, _name)
-    _f.restype, _f.argtypes = _res, _args
+
+
+def _bind(path):
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in _SIGS.items():
+        f = getattr(lib, name)
+        f.restype, f.argtypes = res, args
+    return lib
+
+
+_lib = _bind(_LIB_PATH)
 
 EXPORTS = tuple(_SIGS)
 

@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "librose_delta.so")
 SOURCES = ["plan.cpp", "api.cpp", "kernels.hip"]
 
 
-def build(verbose=False, extra=()):
+def build(verbose=False, extra=(), out=None):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -22,11 +22,11 @@ def build(verbose=False, extra=()):
             cmd += ["-x", "hip", os.path.join(CSRC, s)]
         else:
             cmd += [os.path.join(CSRC, s)]
-    cmd += ["-o", LIB]
+    cmd += ["-o", out or LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":

@@ -78,13 +78,18 @@ extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *
         a.bucket[d].seg_off = buckets[d].seg_off;
     }
     std::memcpy(a.chain_first, p->chain_first, sizeof a.chain_first);
+    std::memcpy(a.block_first, p->block_first, sizeof a.block_first);
     rose_status s = device_tables(p, &a.pieces, &a.tile_piece);
     if (s != ROSE_OK) return s;
     a.old_ptrs = old_ptrs;
     a.new_ptrs = new_ptrs;
-    a.ticket = static_cast<unsigned int *>(workspace);
-    a.desc = reinterpret_cast<unsigned long long *>(static_cast<char *>(workspace) + 256);
+    char *ws = static_cast<char *>(workspace);
+    a.abort_flag = reinterpret_cast<unsigned int *>(ws + rose::kWsAbortOff);
+    a.tile_desc = reinterpret_cast<unsigned long long *>(ws + rose::kWsHeaderBytes);
     a.n_tiles = (int32_t)p->tile_piece.size();
+    a.n_blocks = p->block_first[p->tp];
+    a.block_desc = a.tile_desc + a.n_tiles;
+    a.tp = p->tp;
     a.n_tensors = p->n_tensors;
     return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
 }
@@ -124,6 +129,7 @@ extern "C" rose_status rose_bucket_check(const rose_plan *p, const rose_bucket *
         return ROSE_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return ROSE_ERR_HIP;
     if (required) *required = total;
+    if (total < 0) return ROSE_ERR_HIP;     // the encode launch gave up (see rose_delta_encode)
     return total > bucket->capacity ? ROSE_ERR_CAPACITY : ROSE_OK;
 }
 

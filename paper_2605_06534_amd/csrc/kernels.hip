@@ -58,6 +58,40 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
     return x;
 }
 
+// 128-bit load / store through the global address space (pointers fetched from a table would
+// otherwise be treated as generic and use the slower flat instructions)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) u32x4 global_u32x4;
+__device__ __forceinline__ uint4 gload16(const void *p) {
+    u32x4 v = *reinterpret_cast<const global_u32x4 *>(reinterpret_cast<uintptr_t>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void gstore16(void *p, uint4 v) {
+    u32x4 w = {v.x, v.y, v.z, v.w};
+    *reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(p)) = w;
+}
+
+// Uniform (per-workgroup) table reads through the constant address space, so that they become
+// scalar loads served by the scalar cache instead of vector loads.  Only used for tables that no
+// kernel writes: the plan's piece / tile tables and the caller's pointer tables.
+typedef __attribute__((address_space(4))) const uint32_t const_u32;
+typedef __attribute__((address_space(4))) const uint64_t const_u64;
+__device__ __forceinline__ uint32_t cload32(const void *p) {
+    return *reinterpret_cast<const_u32 *>(reinterpret_cast<uintptr_t>(p));
+}
+__device__ __forceinline__ uint64_t cload64(const void *p) {
+    return *reinterpret_cast<const_u64 *>(reinterpret_cast<uintptr_t>(p));
+}
+__device__ __forceinline__ Piece load_piece(const Piece *p) {
+    static_assert(sizeof(Piece) == 7 * 8, "piece is read as seven 64-bit words");
+    uint64_t w[7];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) w[i] = cload64(reinterpret_cast<const uint64_t *>(p) + i);
+    Piece pc;
+    __builtin_memcpy(&pc, w, sizeof pc);
+    return pc;
+}
+
 // source element of piece-relative local index k
 __device__ __forceinline__ int64_t src_index(const Piece &pc, uint32_t k, bool use_magic) {
     if (pc.flags & kPieceStrided) {
@@ -67,59 +101,98 @@ __device__ __forceinline__ int64_t src_index(const Piece &pc, uint32_t k, bool u
     return pc.src_off + k;
 }
 
-// Load the eight 16-bit patterns at local indices k .. k+7 of a piece (fewer at the ragged end:
-// missing ones read as zero) from a bf16 tensor.
-__device__ __forceinline__ uint4 load8_bf16(const uint16_t *base, const Piece &pc, uint32_t k, bool vec) {
-    uint4 r = make_uint4(0, 0, 0, 0);
-    if (k >= (uint32_t)pc.len) return r;
-    uint32_t valid = (uint32_t)pc.len - k;
-    if (vec && valid >= (uint32_t)kVec) {
-        return *reinterpret_cast<const uint4 *>(base + src_index(pc, k, true));
-    }
-    uint32_t e[kVec];
+// Tile loaders.  A lane's vector j holds the eight 16-bit patterns at piece-relative local indices
+// k .. k+7 with k = k_wave + (j * 64 + lane) * 8.
+//
+// Fast path: the whole tile lies inside the piece and every vector is 16-byte aligned, so all
+// loads are unconditional 128-bit loads issued back to back.
+template <int SRC_F32>
+__device__ __forceinline__ void load_tile_fast(const void *base, const Piece &pc, uint32_t k_wave, int lane,
+                                               uint4 (&out)[kIters]) {
+    if (SRC_F32) {
+        uint4 lo[kIters], hi[kIters];
 #pragma unroll
-    for (int i = 0; i < kVec; ++i) e[i] = ((uint32_t)i < valid) ? base[src_index(pc, k + i, false)] : 0u;
-    r.x = e[0] | (e[1] << 16);
-    r.y = e[2] | (e[3] << 16);
-    r.z = e[4] | (e[5] << 16);
-    r.w = e[6] | (e[7] << 16);
-    return r;
+        for (int j = 0; j < kIters; ++j) {
+            const uint32_t *p = static_cast<const uint32_t *>(base) +
+                                src_index(pc, k_wave + (uint32_t)(j * 64 + lane) * kVec, true);
+            lo[j] = gload16(p);
+            hi[j] = gload16(p + 4);
+        }
+#pragma unroll
+        for (int j = 0; j < kIters; ++j) {
+            out[j].x = pack_rne(lo[j].x, lo[j].y);
+            out[j].y = pack_rne(lo[j].z, lo[j].w);
+            out[j].z = pack_rne(hi[j].x, hi[j].y);
+            out[j].w = pack_rne(hi[j].z, hi[j].w);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kIters; ++j)
+            out[j] = gload16(static_cast<const uint16_t *>(base) +
+                             src_index(pc, k_wave + (uint32_t)(j * 64 + lane) * kVec, true));
+    }
 }
 
-// Same for an fp32 master tensor: the eight values are rounded to bf16 on the way in.
-__device__ __forceinline__ uint4 load8_f32(const uint32_t *base, const Piece &pc, uint32_t k, bool vec) {
-    uint4 r = make_uint4(0, 0, 0, 0);
-    if (k >= (uint32_t)pc.len) return r;
-    uint32_t valid = (uint32_t)pc.len - k;
-    if (vec && valid >= (uint32_t)kVec) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(base + src_index(pc, k, true));
-        uint4 a = p[0], b = p[1];
-        r.x = pack_rne(a.x, a.y);
-        r.y = pack_rne(a.z, a.w);
-        r.z = pack_rne(b.x, b.y);
-        r.w = pack_rne(b.z, b.w);
-        return r;
+// General path (ragged last tile of a piece, shapes or pointers that are not multiples of 16
+// bytes): one vector, element by element; patterns past the end of the piece read as zero.
+template <int SRC_F32>
+__device__ __forceinline__ uint4 load_vec_general(const void *base, const Piece &pc, uint32_t k) {
+    // deliberately one element at a time in a rolled loop: this path is rare and must stay small
+    uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+#pragma unroll 1
+    for (uint32_t i = 0; i < (uint32_t)kVec; ++i) {
+        uint32_t v = 0;
+        if (k + i < (uint32_t)pc.len) {
+            int64_t s = src_index(pc, k + i, false);
+            v = SRC_F32 ? rne_bf16(static_cast<const uint32_t *>(base)[s])
+                        : (uint32_t) static_cast<const uint16_t *>(base)[s];
+        }
+        v <<= (i & 1u) * 16u;
+        const uint32_t q = i >> 1;
+        w0 |= (q == 0) ? v : 0u;
+        w1 |= (q == 1) ? v : 0u;
+        w2 |= (q == 2) ? v : 0u;
+        w3 |= (q == 3) ? v : 0u;
     }
-    uint32_t e[kVec];
-#pragma unroll
-    for (int i = 0; i < kVec; ++i)
-        e[i] = ((uint32_t)i < valid) ? rne_bf16(base[src_index(pc, k + i, false)]) : 0u;
-    r.x = e[0] | (e[1] << 16);
-    r.y = e[2] | (e[3] << 16);
-    r.z = e[4] | (e[5] << 16);
-    r.w = e[6] | (e[7] << 16);
-    return r;
+    return make_uint4(w0, w1, w2, w3);
 }
+
+__device__ __forceinline__ uint4 xor4(uint4 a, uint4 b) { return make_uint4(a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w); }
 
 // ---------------------------------------------------------------------------------------------
-// look-back descriptors: one 64-bit word per tile, status in the top two bits, count below.
-// Published and polled with relaxed device-scope atomics: the word carries everything a
-// successor needs, so no other memory has to be ordered with it.
+// Prefix sums across workgroups.
+//
+// Every tile needs the number of entries that earlier tiles of its chain (= destination shard)
+// produce.  Tiles are grouped in blocks of kBlock consecutive tiles of a chain.  Each tile first
+// publishes its own count ("aggregate").  The LAST tile of a block is the block's leader: one of
+// its waves reads the block's aggregates in a single 64-wide load, scans them, publishes the block
+// total, looks back over earlier BLOCK descriptors (64 blocks = 4096 tiles per load) for the
+// block's starting offset, and then writes every tile of the block its exclusive prefix.  The
+// other tiles only poll their own word.  So no tile ever walks a long chain, and a descriptor is
+// polled by one reader (tile words) or a few (block words).
+//
+// A descriptor is one 64-bit word, status in the top two bits, value below, written and read with
+// relaxed device-scope atomics: the word carries all a reader needs, nothing else is ordered by it.
+//
+// Progress: workgroup w owns tiles w, w + grid, w + 2 grid, ... and the whole grid is resident at
+// once (the launcher sizes it from the occupancy query), so every tile's owner is running.  A
+// tile publishes its aggregate before it waits; a leader waits only for aggregates of its block
+// and for earlier blocks; other tiles wait only for their leader.  Waits are bounded anyway: after
+// ROSE_SPIN_LIMIT failed polls, or once the abort flag is set, a wave stops waiting, the flag is
+// set, and the launch is reported as failed; every wave always reaches the end of the kernel.
 // ---------------------------------------------------------------------------------------------
 constexpr u64 kStatusShift = 62;
-constexpr u64 kStatusAggregate = 1;   // value = this tile's own count
-constexpr u64 kStatusPrefix = 2;      // value = count of this tile and all before it in the chain
+constexpr u64 kStatusAggregate = 1;   // tile word: the tile's count;  block word: the block's count
+constexpr u64 kStatusPrefix = 2;      // tile word: the tile's exclusive prefix;  block word: count of
+                                      // this block and all earlier blocks of the chain
 constexpr u64 kValueMask = (1ull << kStatusShift) - 1;
+
+#ifndef ROSE_DIAG
+#define ROSE_DIAG 0           // timing experiments only: 1 skips the cross-tile prefix, 2 skips the bucket writes
+#endif
+#ifndef ROSE_SPIN_LIMIT
+#define ROSE_SPIN_LIMIT (1u << 22)   // failed polls after which a wave gives up and flags the launch
+#endif
 
 __device__ __forceinline__ void desc_store(u64 *p, u64 v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -128,138 +201,229 @@ __device__ __forceinline__ u64 desc_load(u64 *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__global__ void reset_kernel(u64 *desc, unsigned int *ticket, int32_t n_tiles) {
+__global__ void reset_kernel(u64 *desc, unsigned int *abort_flag, int64_t n_desc) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *ticket = 0;
-    for (; i < n_tiles; i += (int64_t)gridDim.x * blockDim.x) desc[i] = 0;
+    if (i == 0) *abort_flag = 0;
+    for (; i < n_desc; i += (int64_t)gridDim.x * blockDim.x) desc[i] = 0;
+}
+
+// After encode: if any wave gave up waiting, mark every bucket as invalid (total = -1) so that
+// rose_bucket_check reports it and apply does nothing.
+__global__ void finalize_kernel(EncodeArgs a) {
+    if (threadIdx.x < (unsigned)a.tp && *a.abort_flag) a.bucket[threadIdx.x].seg_off[a.n_tensors] = -1;
+}
+
+// bounded wait bookkeeping; returns false when the wave must stop waiting
+__device__ __forceinline__ bool keep_waiting(unsigned int *abort_flag, unsigned int &spins, int lane) {
+    if (++spins > ROSE_SPIN_LIMIT ||
+        ((spins & 63u) == 0 && __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+        if (lane == 0) __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+    }
+    __builtin_amdgcn_s_sleep(2);
+    return true;
+}
+
+// sum of a 64-bit value over the wave
+__device__ __forceinline__ u64 wave_sum64(u64 v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+    return v;
+}
+
+// Offset of block `blk` (index into block_desc) inside its chain whose first block is
+// `blk_first`: the published total of all earlier blocks.  One wave; each step reads 64 earlier
+// block words (nearest first), needs every word nearer than the first prefix to hold at least an
+// aggregate, and sums them.
+__device__ __forceinline__ bool block_look_back(u64 *block_desc, unsigned int *abort_flag, int32_t blk,
+                                                int32_t blk_first, int lane, u64 *out) {
+    u64 excl = 0;
+    int32_t look = blk - 1;
+    unsigned int spins = 0;
+    for (;;) {
+        int32_t at = look - lane;
+        u64 v = (at >= blk_first) ? desc_load(block_desc + at) : (kStatusPrefix << kStatusShift);
+        u64 st = v >> kStatusShift;
+        u64 pref = __ballot(st == kStatusPrefix);
+        u64 empty = __ballot(st == 0);
+        int first_pref = pref ? __ffsll((long long)pref) - 1 : 64;
+        u64 need = (first_pref >= 63) ? ~0ull : ((1ull << (first_pref + 1)) - 1);
+        if (empty & need) {
+            if (!keep_waiting(abort_flag, spins, lane)) return false;
+            continue;
+        }
+        excl += wave_sum64((lane <= first_pref) ? (v & kValueMask) : 0);
+        if (pref) break;
+        look -= 64;
+    }
+    *out = excl;
+    return true;
+}
+
+// Exclusive prefix of `tile` (own count `total`) in its chain; executed by one whole wave.
+__device__ __forceinline__ bool tile_prefix(const EncodeArgs &a, int32_t tile, int32_t shard, uint32_t total,
+                                            int lane, u64 *out) {
+    const int32_t chain_first = a.chain_first[shard];
+    const int32_t chain_last = a.chain_first[shard + 1] - 1;
+    const int32_t rel = tile - chain_first;
+    const int32_t q = rel & (kBlock - 1);                       // position inside the block
+    const int32_t blk_first = a.block_first[shard];
+    const int32_t blk = blk_first + rel / kBlock;
+    unsigned int spins = 0;
+    if (q != kBlock - 1 && tile != chain_last) {
+        // ordinary tile: publish the count, wait for the leader's answer in the same word
+        if (lane == 0) desc_store(a.tile_desc + tile, (kStatusAggregate << kStatusShift) | total);
+        for (;;) {
+            u64 v = desc_load(a.tile_desc + tile);
+            if ((v >> kStatusShift) == kStatusPrefix) {
+                *out = v & kValueMask;
+                return true;
+            }
+            if (!keep_waiting(a.abort_flag, spins, lane)) return false;
+        }
+    }
+    // leader: lane i < q takes the aggregate of the block's tile i, lane q this tile's own count
+    u64 agg;
+    for (;;) {
+        u64 v = (lane < q) ? desc_load(a.tile_desc + (tile - q + lane)) : ((kStatusAggregate << kStatusShift) | 0);
+        if (__ballot((v >> kStatusShift) == 0) == 0) {
+            agg = (lane < q) ? (v & kValueMask) : (lane == q ? (u64)total : 0);
+            break;
+        }
+        if (!keep_waiting(a.abort_flag, spins, lane)) return false;
+    }
+    const uint32_t incl = wave_incl_scan((uint32_t)agg);        // <= 64 tiles * kTile entries
+    const uint32_t block_total = __shfl(incl, 63, 64);
+    u64 block_excl = 0;
+    bool ok = true;
+    if (blk > blk_first) {
+        if (lane == 0) desc_store(a.block_desc + blk, (kStatusAggregate << kStatusShift) | block_total);
+        ok = block_look_back(a.block_desc, a.abort_flag, blk, blk_first, lane, &block_excl);
+    }
+    // published even after giving up, so that nobody keeps waiting on this block
+    if (lane == 0) desc_store(a.block_desc + blk, (kStatusPrefix << kStatusShift) | (block_excl + block_total));
+    const u64 excl = block_excl + (incl - (uint32_t)agg);
+    if (lane < q) desc_store(a.tile_desc + (tile - q + lane), (kStatusPrefix << kStatusShift) | excl);
+    *out = __shfl(excl, q, 64);
+    return ok;
 }
 
 // ---------------------------------------------------------------------------------------------
-// encode: one workgroup per tile, tiles handed out by a ticket so that a tile's predecessors in
-// its chain have always started.
+// encode: persistent workgroups walk the tiles: workgroup w takes tiles w, w + grid, ...
+// Per tile:
 //   1. issue all 128-bit loads of the tile (old and new), 2. XOR -> 8-bit change mask per vector,
-//   3. wave prefix sums of the popcounts, wave totals through LDS, 4. wave 0 publishes the tile
-//   count and looks back along the shard's chain for its exclusive prefix, 5. every lane writes its
-//   changed (local index, new pattern) pairs at bucket position prefix + rank.
-// Inside a tile wave w covers a contiguous quarter and walks it in kIters steps of 512 elements,
+//   3. wave prefix sums of the popcounts, wave totals through LDS, 4. wave 0 obtains the tile's
+//   exclusive prefix in its chain (see above), 5. every lane writes its changed
+//   (local index, new pattern) pairs at bucket position prefix + rank.
+// Inside a tile wave w covers a contiguous part and walks it in kIters steps of 512 elements,
 // so the order (wave, step, lane, element) is ascending local index.
 // ---------------------------------------------------------------------------------------------
 template <int NEW_F32>
 __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
-    __shared__ int32_t s_tile;
     __shared__ uint32_t s_wave_total[kWaves];
     __shared__ u64 s_excl;
-
-    if (threadIdx.x == 0)
-        s_tile = (int32_t)__hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    const int32_t tile = __builtin_amdgcn_readfirstlane(s_tile);   // uniform: keep it scalar
-    if (tile >= a.n_tiles) return;
-
-    const Piece pc = a.pieces[a.tile_piece[tile]];
+    __shared__ int32_t s_ok;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint16_t *old_base = static_cast<const uint16_t *>(a.old_ptrs[pc.tensor]);
-    const void *new_base = a.new_ptrs[pc.tensor];
-    const bool vec = (pc.flags & kPieceVec) &&
-                     ((((uintptr_t)old_base) | ((uintptr_t)new_base)) & 15u) == 0;
-    const uint32_t k_wave = (uint32_t)(tile - pc.first_tile) * (uint32_t)kTile + (uint32_t)wave * kWaveSpan;
 
-    uint4 nv[kIters];
-    uint32_t mask[kIters];
-    {
-        uint4 ov[kIters];
-#pragma unroll
-        for (int j = 0; j < kIters; ++j) {
-            uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
-            ov[j] = load8_bf16(old_base, pc, k, vec);
-            nv[j] = NEW_F32 ? load8_f32(static_cast<const uint32_t *>(new_base), pc, k, vec)
-                            : load8_bf16(static_cast<const uint16_t *>(new_base), pc, k, vec);
-        }
-#pragma unroll
-        for (int j = 0; j < kIters; ++j) {
-            uint4 x = make_uint4(ov[j].x ^ nv[j].x, ov[j].y ^ nv[j].y, ov[j].z ^ nv[j].z, ov[j].w ^ nv[j].w);
-            mask[j] = nz16_mask(x);
-        }
-    }
+    for (int32_t tile = (int32_t)blockIdx.x; tile < a.n_tiles; tile += (int32_t)gridDim.x) {
+        const Piece pc = load_piece(a.pieces + cload32(a.tile_piece + tile));
+        const uint16_t *old_base = reinterpret_cast<const uint16_t *>(cload64(a.old_ptrs + pc.tensor));
+        const void *new_base = reinterpret_cast<const void *>(cload64(a.new_ptrs + pc.tensor));
+        const uint32_t k_tile = (uint32_t)(tile - pc.first_tile) * (uint32_t)kTile;
+        const uint32_t k_wave = k_tile + (uint32_t)wave * kWaveSpan;
+        // uniform choice: full, aligned tile -> straight 128-bit loads
+        const bool fast = (pc.flags & kPieceVec) && k_tile + (uint32_t)kTile <= (uint32_t)pc.len &&
+                          ((((uintptr_t)old_base) | ((uintptr_t)new_base)) & 15u) == 0;
 
-    // exclusive rank of each of this lane's vectors inside the wave's span
-    uint32_t rank[kIters];
-    uint32_t wave_total = 0;
+        uint4 nv[kIters];
+        uint32_t mask[kIters];
+        if (fast) {
+            uint4 ov[kIters];
+            load_tile_fast<0>(old_base, pc, k_wave, lane, ov);
+            load_tile_fast<NEW_F32>(new_base, pc, k_wave, lane, nv);
 #pragma unroll
-    for (int j = 0; j < kIters; ++j) {
-        uint32_t c = __popc(mask[j]);
-        uint32_t inc = wave_incl_scan(c);
-        rank[j] = wave_total + inc - c;
-        wave_total += __shfl(inc, 63, 64);
-    }
-    if (lane == 0) s_wave_total[wave] = wave_total;
-    __syncthreads();
-
-    uint32_t wave_excl = 0, tile_total = 0;
+            for (int j = 0; j < kIters; ++j) mask[j] = nz16_mask(xor4(ov[j], nv[j]));
+        } else {
+            // kept as a rolled loop (one vector in flight) so that this rare path does not set
+            // the kernel's register budget; the selects put the result into static slots
+#pragma unroll 1
+            for (int j = 0; j < kIters; ++j) {
+                uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
+                uint4 o = load_vec_general<0>(old_base, pc, k);
+                uint4 n = load_vec_general<NEW_F32>(new_base, pc, k);
+                uint32_t m = nz16_mask(xor4(o, n));
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        uint32_t c = s_wave_total[w];
-        if (w < wave) wave_excl += c;
-        tile_total += c;
-    }
-
-    const int32_t chain_first = a.chain_first[pc.shard];
-    if (wave == 0) {
-        u64 excl = 0;
-        if (tile > chain_first) {
-            if (lane == 0) desc_store(a.desc + tile, (kStatusAggregate << kStatusShift) | tile_total);
-            int32_t look = tile - 1;      // lane 0 reads the nearest predecessor
-            for (;;) {
-                int32_t at = look - lane;
-                u64 v = (at >= chain_first) ? desc_load(a.desc + at) : (kStatusPrefix << kStatusShift);
-                u64 st = v >> kStatusShift;
-                u64 empty = __ballot(st == 0);
-                u64 pref = __ballot(st == kStatusPrefix);
-                // lanes nearer than the first prefix must all be published
-                int first_pref = pref ? __ffsll((long long)pref) - 1 : 64;
-                u64 need = (first_pref >= 63) ? ~0ull : ((1ull << (first_pref + 1)) - 1);
-                if (empty & need) {
-                    __builtin_amdgcn_s_sleep(1);
-                    continue;
+                for (int jj = 0; jj < kIters; ++jj) {
+                    if (jj == j) {
+                        nv[jj] = n;
+                        mask[jj] = m;
+                    }
                 }
-                u64 contrib = (lane <= first_pref) ? (v & kValueMask) : 0;
-                // wave sum of 64-bit values
-#pragma unroll
-                for (int s = 32; s >= 1; s >>= 1) contrib += __shfl_xor(contrib, s, 64);
-                excl += contrib;
-                if (pref) break;
-                look -= 64;
             }
         }
-        if (lane == 0) {
-            desc_store(a.desc + tile, (kStatusPrefix << kStatusShift) | (excl + tile_total));
-            s_excl = excl;
-        }
-    }
-    __syncthreads();
-    const u64 tile_excl = s_excl;
 
-    const BucketDev b = a.bucket[pc.shard];
-    if (threadIdx.x == 0) {
-        if ((pc.flags & kPieceFirst) && tile == pc.first_tile) b.seg_off[pc.tensor] = (int64_t)tile_excl;
-        if (tile == a.chain_first[pc.shard + 1] - 1) b.seg_off[a.n_tensors] = (int64_t)(tile_excl + tile_total);
-    }
-
-    const u64 wave_base = tile_excl + wave_excl;
+        // exclusive rank of each of this lane's vectors inside the wave's span
+        uint32_t rank[kIters];
+        uint32_t wave_total = 0;
 #pragma unroll
-    for (int j = 0; j < kIters; ++j) {
-        uint32_t m = mask[j];
-        u64 pos = wave_base + rank[j];
-        uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
-        while (m) {
-            uint32_t e = __ffs(m) - 1;
-            m &= m - 1;
-            if (pos < (u64)b.capacity) {
-                b.idx[pos] = (int32_t)(local0 + e);
-                b.val[pos] = (uint16_t)pick16(nv[j], e);
-            }
-            ++pos;
+        for (int j = 0; j < kIters; ++j) {
+            uint32_t c = __popc(mask[j]);
+            uint32_t inc = wave_incl_scan(c);
+            rank[j] = wave_total + inc - c;
+            wave_total += __shfl(inc, 63, 64);
         }
+        if (lane == 0) s_wave_total[wave] = wave_total;
+        __syncthreads();
+
+        uint32_t wave_excl = 0, tile_total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            uint32_t c = s_wave_total[w];
+            if (w < wave) wave_excl += c;
+            tile_total += c;
+        }
+
+        if (wave == 0) {
+            u64 excl = 0;
+            bool ok = true;
+#if !(ROSE_DIAG & 1)
+            ok = tile_prefix(a, tile, pc.shard, tile_total, lane, &excl);
+#endif
+            if (lane == 0) {
+                s_excl = excl;
+                s_ok = ok ? 1 : 0;
+            }
+        }
+        __syncthreads();
+        const u64 tile_excl = s_excl;
+        const bool ok = s_ok != 0;
+
+        const BucketDev b = a.bucket[pc.shard];
+        if (threadIdx.x == 0 && ok) {
+            if ((pc.flags & kPieceFirst) && tile == pc.first_tile) b.seg_off[pc.tensor] = (int64_t)tile_excl;
+            if (tile == a.chain_first[pc.shard + 1] - 1) b.seg_off[a.n_tensors] = (int64_t)(tile_excl + tile_total);
+        }
+
+        if (ok && !(ROSE_DIAG & 2)) {
+            const u64 wave_base = tile_excl + wave_excl;
+#pragma unroll
+            for (int j = 0; j < kIters; ++j) {
+                uint32_t m = mask[j];
+                u64 pos = wave_base + rank[j];
+                uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
+                while (m) {
+                    uint32_t e = __ffs(m) - 1;
+                    m &= m - 1;
+                    if (pos < (u64)b.capacity) {
+                        b.idx[pos] = (int32_t)(local0 + e);
+                        b.val[pos] = (uint16_t)pick16(nv[j], e);
+                    }
+                    ++pos;
+                }
+            }
+        }
+        // No barrier is needed before the shared words are reused: each is written only after a
+        // barrier that every wave reaches after its last read of the previous value.
     }
 }
 
@@ -268,9 +432,10 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
 // inside a segment, so neighbouring lanes store into the same or neighbouring lines.
 // ---------------------------------------------------------------------------------------------
 constexpr int kApplyPerLane = 4;
-constexpr int kApplyChunk = kThreads * kApplyPerLane;
+constexpr int kApplyThreads = 256;
+constexpr int kApplyChunk = kApplyThreads * kApplyPerLane;
 
-__global__ __launch_bounds__(kThreads) void apply_kernel(BucketDev b, int32_t n_tensors, void *const *dst_ptrs) {
+__global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors, void *const *dst_ptrs) {
     int64_t total = b.seg_off[n_tensors];
     if (total > b.capacity) total = b.capacity;
     for (int64_t e0 = (int64_t)blockIdx.x * kApplyChunk; e0 < total; e0 += (int64_t)gridDim.x * kApplyChunk) {
@@ -325,29 +490,28 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(BucketDev b, int32_t n_
 template <int NEW_F32>
 __global__ __launch_bounds__(kThreads) void dense_copy_kernel(CopyArgs a) {
     const int32_t tile = a.tile_begin + (int32_t)blockIdx.x;
-    const Piece pc = a.pieces[a.tile_piece[tile]];
+    const Piece pc = load_piece(a.pieces + cload32(a.tile_piece + tile));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const void *new_base = a.new_ptrs[pc.tensor];
-    uint16_t *dst = static_cast<uint16_t *>(a.dst_ptrs[pc.tensor]);
-    const bool vec = (pc.flags & kPieceVec) && ((((uintptr_t)new_base) | ((uintptr_t)dst)) & 15u) == 0;
-    const uint32_t k_wave = (uint32_t)(tile - pc.first_tile) * (uint32_t)kTile + (uint32_t)wave * kWaveSpan;
-    uint4 nv[kIters];
+    const void *new_base = reinterpret_cast<const void *>(cload64(a.new_ptrs + pc.tensor));
+    uint16_t *dst = reinterpret_cast<uint16_t *>(cload64(a.dst_ptrs + pc.tensor));
+    const uint32_t k_tile = (uint32_t)(tile - pc.first_tile) * (uint32_t)kTile;
+    const uint32_t k_wave = k_tile + (uint32_t)wave * kWaveSpan;
+    const bool fast = (pc.flags & kPieceVec) && k_tile + (uint32_t)kTile <= (uint32_t)pc.len &&
+                      ((((uintptr_t)new_base) | ((uintptr_t)dst)) & 15u) == 0;
+    if (fast) {
+        uint4 nv[kIters];
+        load_tile_fast<NEW_F32>(new_base, pc, k_wave, lane, nv);
 #pragma unroll
-    for (int j = 0; j < kIters; ++j) {
-        uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
-        nv[j] = NEW_F32 ? load8_f32(static_cast<const uint32_t *>(new_base), pc, k, vec)
-                        : load8_bf16(static_cast<const uint16_t *>(new_base), pc, k, vec);
-    }
+        for (int j = 0; j < kIters; ++j)
+            gstore16(dst + (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec, nv[j]);
+    } else {
+#pragma unroll 1
+        for (int j = 0; j < kIters; ++j) {
+            uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
+            uint4 n = load_vec_general<NEW_F32>(new_base, pc, k);
 #pragma unroll
-    for (int j = 0; j < kIters; ++j) {
-        uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
-        if (k >= (uint32_t)pc.len) continue;
-        uint32_t valid = (uint32_t)pc.len - k;
-        uint16_t *out = dst + (uint32_t)pc.local_base + k;
-        if (vec && valid >= (uint32_t)kVec) {
-            *reinterpret_cast<uint4 *>(out) = nv[j];
-        } else {
-            for (uint32_t i = 0; i < valid && i < (uint32_t)kVec; ++i) out[i] = (uint16_t)pick16(nv[j], i);
+            for (uint32_t i = 0; i < (uint32_t)kVec; ++i)
+                if (k + i < (uint32_t)pc.len) dst[(uint32_t)pc.local_base + k + i] = (uint16_t)pick16(n, i);
         }
     }
 }
@@ -355,57 +519,87 @@ __global__ __launch_bounds__(kThreads) void dense_copy_kernel(CopyArgs a) {
 // ---------------------------------------------------------------------------------------------
 // bandwidth probe: grid-stride 128-bit copy, or read-only with a checksum
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void bw_copy_kernel(const uint4 *src, uint4 *dst, size_t n16) {
-    size_t i = (size_t)blockIdx.x * (kThreads * 4) + threadIdx.x;
-    const size_t step = (size_t)gridDim.x * (kThreads * 4);
+constexpr int kBwThreads = 256;
+
+__global__ __launch_bounds__(256) void bw_copy_kernel(const uint4 *src, uint4 *dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * (kBwThreads * 4) + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * (kBwThreads * 4);
     for (; i < n16; i += step) {
         uint4 v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            size_t at = i + (size_t)j * kThreads;
+            size_t at = i + (size_t)j * kBwThreads;
             v[j] = at < n16 ? src[at] : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            size_t at = i + (size_t)j * kThreads;
+            size_t at = i + (size_t)j * kBwThreads;
             if (at < n16) dst[at] = v[j];
         }
     }
 }
 
-__global__ __launch_bounds__(kThreads) void bw_read_kernel(const uint4 *src, size_t n16, u64 *sink) {
-    size_t i = (size_t)blockIdx.x * (kThreads * 4) + threadIdx.x;
-    const size_t step = (size_t)gridDim.x * (kThreads * 4);
+__global__ __launch_bounds__(256) void bw_read_kernel(const uint4 *src, size_t n16, u64 *sink) {
+    size_t i = (size_t)blockIdx.x * (kBwThreads * 4) + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * (kBwThreads * 4);
     uint32_t acc = 0;
     for (; i < n16; i += step) {
         uint4 v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            size_t at = i + (size_t)j * kThreads;
+            size_t at = i + (size_t)j * kBwThreads;
             v[j] = at < n16 ? src[at] : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc += v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
     }
-    // the checksum keeps the loads alive: one atomic per wave
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s, 64);
-    if ((threadIdx.x & 63) == 0) atomicAdd(sink, (u64)acc);
+    // The data-dependent test keeps the loads alive; it is true for about one lane in 2^32, so
+    // the probe is not slowed down by atomics on one address.
+    if (acc == 0x9E3779B9u) atomicAdd(sink, 1ull);
 }
 
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
+// workgroups per CU the encode grid may use (bounded by what fits at once)
+#ifndef ROSE_WGS_PER_CU
+#define ROSE_WGS_PER_CU 8
+#endif
+
+static int encode_grid(int new_is_f32, int32_t n_tiles, int *grid) {
+    static int cached[2] = {0, 0};          // per kernel variant; the device set is homogeneous
+    if (!cached[new_is_f32]) {
+        int dev = 0, cus = 0, per_cu = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = new_is_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<1>, kThreads, 0)
+                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<0>, kThreads, 0);
+        if (e != hipSuccess) return (int)e;
+        if (per_cu < 1 || cus < 1) return (int)hipErrorInvalidValue;
+        if (per_cu > ROSE_WGS_PER_CU) per_cu = ROSE_WGS_PER_CU;
+        cached[new_is_f32] = cus * per_cu;
+    }
+    *grid = cached[new_is_f32] < n_tiles ? cached[new_is_f32] : n_tiles;
+    return 0;
+}
+
 int launch_encode(const EncodeArgs &a, int new_is_f32, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    int grid = 0;
+    int rc = encode_grid(new_is_f32, a.n_tiles, &grid);
+    if (rc) return rc;
     int reset_blocks = (a.n_tiles + 1023) / 1024;
     if (reset_blocks < 1) reset_blocks = 1;
     if (reset_blocks > 2048) reset_blocks = 2048;
-    hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, a.desc, a.ticket, a.n_tiles);
+    // tile and block descriptors are one contiguous array
+    hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, a.tile_desc, a.abort_flag,
+                       (int64_t)a.n_tiles + a.n_blocks);
     if (new_is_f32)
-        hipLaunchKernelGGL(encode_kernel<1>, dim3(a.n_tiles), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL(encode_kernel<1>, dim3(grid), dim3(kThreads), 0, st, a);
     else
-        hipLaunchKernelGGL(encode_kernel<0>, dim3(a.n_tiles), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL(encode_kernel<0>, dim3(grid), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, st, a);
     return (int)hipGetLastError();
 }
 
@@ -413,7 +607,7 @@ int launch_apply(const BucketDev &b, int32_t n_tensors, void *const *dst_ptrs, v
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = (b.capacity + kApplyChunk - 1) / kApplyChunk;
     int blocks = chunks < 1 ? 1 : (chunks > 256 * 16 ? 256 * 16 : (int)chunks);
-    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kThreads), 0, st, b, n_tensors, dst_ptrs);
+    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, dst_ptrs);
     return (int)hipGetLastError();
 }
 
@@ -431,13 +625,13 @@ int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, vo
     hipStream_t st = static_cast<hipStream_t>(stream);
     size_t n16 = bytes / 16;
     if (n16 == 0) return 0;
-    size_t want = (n16 + kThreads * 4 - 1) / (kThreads * 4);
+    size_t want = (n16 + kBwThreads * 4 - 1) / (kBwThreads * 4);
     int blocks = want > 256 * 32 ? 256 * 32 : (int)want;
     if (dst)
-        hipLaunchKernelGGL(bw_copy_kernel, dim3(blocks), dim3(kThreads), 0, st,
+        hipLaunchKernelGGL(bw_copy_kernel, dim3(blocks), dim3(kBwThreads), 0, st,
                            static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
     else
-        hipLaunchKernelGGL(bw_read_kernel, dim3(blocks), dim3(kThreads), 0, st,
+        hipLaunchKernelGGL(bw_read_kernel, dim3(blocks), dim3(kBwThreads), 0, st,
                            static_cast<const uint4 *>(src), n16, reinterpret_cast<u64 *>(sink));
     return (int)hipGetLastError();
 }

@@ -163,6 +163,11 @@ extern "C" rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, i
             }
         }
         for (int32_t d = tp; d <= ROSE_MAX_TP; ++d) p->chain_first[d] = (int32_t)n_tiles;
+        int32_t n_blocks = 0;
+        for (int32_t d = 0; d <= ROSE_MAX_TP; ++d) {
+            p->block_first[d] = n_blocks;
+            if (d < tp) n_blocks += (p->chain_first[d + 1] - p->chain_first[d] + rose::kBlock - 1) / rose::kBlock;
+        }
     } catch (...) {
         delete p;
         return ROSE_ERR_ARG;
@@ -202,8 +207,9 @@ extern "C" rose_status rose_plan_n_tiles(const rose_plan *p, int64_t *n_tiles) {
 
 extern "C" rose_status rose_plan_workspace_bytes(const rose_plan *p, size_t *bytes) {
     if (!p || !bytes) return ROSE_ERR_ARG;
-    // 256 bytes of header (ticket counter) + one 64-bit descriptor per tile
-    *bytes = 256 + p->tile_piece.size() * sizeof(unsigned long long);
+    // header + one 64-bit descriptor per tile + one per block of tiles
+    *bytes = rose::kWsHeaderBytes +
+             (p->tile_piece.size() + (size_t)p->block_first[p->tp]) * sizeof(unsigned long long);
     return ROSE_OK;
 }
 

@@ -12,7 +12,10 @@ namespace rose {
 
 // Tile geometry of the encode / dense-copy kernels: one workgroup of kThreads lanes walks one
 // tile; a lane takes kIters vectors of kVec 16-bit elements (one 128-bit load each).
-constexpr int kThreads = 256;
+#ifndef ROSE_THREADS
+#define ROSE_THREADS 256
+#endif
+constexpr int kThreads = ROSE_THREADS;
 constexpr int kWaves = kThreads / 64;
 constexpr int kVec = 8;
 #ifndef ROSE_ITERS
@@ -63,11 +66,23 @@ struct EncodeArgs {
     const int32_t *tile_piece;
     const void *const *old_ptrs;
     const void *const *new_ptrs;
-    unsigned long long *desc;               // one look-back descriptor per tile
-    unsigned int *ticket;
+    int32_t block_first[ROSE_MAX_TP + 1];   // first block descriptor of each shard's chain
+    unsigned long long *tile_desc;          // one descriptor per tile
+    unsigned long long *block_desc;         // one descriptor per block of kBlock tiles of a chain
+    unsigned int *abort_flag;               // workspace header: set when a wait gave up
     int32_t n_tiles;
+    int32_t n_blocks;
     int32_t n_tensors;
+    int32_t tp;
 };
+
+// Tiles of one chain are grouped in blocks of kBlock; the last tile of a block gathers the
+// block's counts and hands every tile of the block its prefix.
+constexpr int kBlock = 64;
+
+// workspace layout (bytes): header, tile descriptors, block descriptors
+constexpr size_t kWsAbortOff = 0;
+constexpr size_t kWsHeaderBytes = 256;
 
 struct CopyArgs {
     const Piece *pieces;
@@ -100,6 +115,7 @@ struct rose_plan {
     std::vector<rose::Piece> pieces;
     std::vector<int32_t> tile_piece;           // piece of each tile
     int32_t chain_first[ROSE_MAX_TP + 1] = {0};
+    int32_t block_first[ROSE_MAX_TP + 1] = {0};
     // device copies of pieces / tile_piece, made on first use on a device
     mutable std::mutex mu;
     mutable int device = -1;
