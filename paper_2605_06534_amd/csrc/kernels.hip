@@ -105,32 +105,49 @@ __device__ __forceinline__ int64_t src_index(const Piece &pc, uint32_t k, bool u
 // k .. k+7 with k = k_wave + (j * 64 + lane) * 8.
 //
 // Fast path: the whole tile lies inside the piece and every vector is 16-byte aligned, so all
-// loads are unconditional 128-bit loads issued back to back.
+// loads are unconditional 128-bit loads issued back to back.  Loading (raw registers) is split
+// from conversion so that a tile's loads can be issued long before its data is needed.
+template <int SRC_F32> struct RawTile;
+template <> struct RawTile<0> { uint4 v[kIters]; };
+template <> struct RawTile<1> { uint4 lo[kIters], hi[kIters]; };
+
+// `limit` is the piece length for a tile that reaches past the end of its piece (vectors that do
+// not fit entirely read as zero) and 0xFFFFFFFF for a full tile.
+__device__ __forceinline__ void load_raw(const void *base, const Piece &pc, uint32_t k_wave, int lane,
+                                         uint32_t limit, RawTile<0> &r) {
+#pragma unroll
+    for (int j = 0; j < kIters; ++j) {
+        const uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
+        r.v[j] = make_uint4(0, 0, 0, 0);
+        if (k + kVec <= limit) r.v[j] = gload16(static_cast<const uint16_t *>(base) + src_index(pc, k, true));
+    }
+}
+__device__ __forceinline__ void load_raw(const void *base, const Piece &pc, uint32_t k_wave, int lane,
+                                         uint32_t limit, RawTile<1> &r) {
+#pragma unroll
+    for (int j = 0; j < kIters; ++j) {
+        const uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
+        r.lo[j] = r.hi[j] = make_uint4(0, 0, 0, 0);
+        if (k + kVec <= limit) {
+            const uint32_t *p = static_cast<const uint32_t *>(base) + src_index(pc, k, true);
+            r.lo[j] = gload16(p);
+            r.hi[j] = gload16(p + 4);
+        }
+    }
+}
+__device__ __forceinline__ uint4 raw_to_bf16(const RawTile<0> &r, int j) { return r.v[j]; }
+__device__ __forceinline__ uint4 raw_to_bf16(const RawTile<1> &r, int j) {
+    return make_uint4(pack_rne(r.lo[j].x, r.lo[j].y), pack_rne(r.lo[j].z, r.lo[j].w),
+                      pack_rne(r.hi[j].x, r.hi[j].y), pack_rne(r.hi[j].z, r.hi[j].w));
+}
+
 template <int SRC_F32>
 __device__ __forceinline__ void load_tile_fast(const void *base, const Piece &pc, uint32_t k_wave, int lane,
                                                uint4 (&out)[kIters]) {
-    if (SRC_F32) {
-        uint4 lo[kIters], hi[kIters];
+    RawTile<SRC_F32> r;
+    load_raw(base, pc, k_wave, lane, 0xFFFFFFFFu, r);
 #pragma unroll
-        for (int j = 0; j < kIters; ++j) {
-            const uint32_t *p = static_cast<const uint32_t *>(base) +
-                                src_index(pc, k_wave + (uint32_t)(j * 64 + lane) * kVec, true);
-            lo[j] = gload16(p);
-            hi[j] = gload16(p + 4);
-        }
-#pragma unroll
-        for (int j = 0; j < kIters; ++j) {
-            out[j].x = pack_rne(lo[j].x, lo[j].y);
-            out[j].y = pack_rne(lo[j].z, lo[j].w);
-            out[j].z = pack_rne(hi[j].x, hi[j].y);
-            out[j].w = pack_rne(hi[j].z, hi[j].w);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < kIters; ++j)
-            out[j] = gload16(static_cast<const uint16_t *>(base) +
-                             src_index(pc, k_wave + (uint32_t)(j * 64 + lane) * kVec, true));
-    }
+    for (int j = 0; j < kIters; ++j) out[j] = raw_to_bf16(r, j);
 }
 
 // General path (ragged last tile of a piece, shapes or pointers that are not multiples of 16
@@ -163,23 +180,25 @@ __device__ __forceinline__ uint4 xor4(uint4 a, uint4 b) { return make_uint4(a.x 
 // Prefix sums across workgroups.
 //
 // Every tile needs the number of entries that earlier tiles of its chain (= destination shard)
-// produce.  Tiles are grouped in blocks of kBlock consecutive tiles of a chain.  Each tile first
-// publishes its own count ("aggregate").  The LAST tile of a block is the block's leader: one of
-// its waves reads the block's aggregates in a single 64-wide load, scans them, publishes the block
-// total, looks back over earlier BLOCK descriptors (64 blocks = 4096 tiles per load) for the
-// block's starting offset, and then writes every tile of the block its exclusive prefix.  The
-// other tiles only poll their own word.  So no tile ever walks a long chain, and a descriptor is
-// polled by one reader (tile words) or a few (block words).
+// produce.  Tiles are grouped in blocks of kBlock consecutive tiles of a chain.  A worker publishes
+// each tile's count ("aggregate") in the tile's descriptor word and moves on.  A few workgroups of
+// the grid do not walk tiles: each of their waves SERVES blocks (block s, s + n_servers, ...): it
+// reads the block's 64 aggregates with one load per poll, scans them, publishes the block total,
+// looks back over earlier BLOCK words (64 blocks = 4096 tiles per load) for the block's offset and
+// writes every tile of the block its exclusive prefix into the tile's word.  Workers read only
+// their own tiles' words, so no worker ever walks a chain or waits for a slower worker's tile
+// other than through the answer it needs.
 //
 // A descriptor is one 64-bit word, status in the top two bits, value below, written and read with
 // relaxed device-scope atomics: the word carries all a reader needs, nothing else is ordered by it.
 //
-// Progress: workgroup w owns tiles w, w + grid, w + 2 grid, ... and the whole grid is resident at
-// once (the launcher sizes it from the occupancy query), so every tile's owner is running.  A
-// tile publishes its aggregate before it waits; a leader waits only for aggregates of its block
-// and for earlier blocks; other tiles wait only for their leader.  Waits are bounded anyway: after
-// ROSE_SPIN_LIMIT failed polls, or once the abort flag is set, a wave stops waiting, the flag is
-// set, and the launch is reported as failed; every wave always reaches the end of the kernel.
+// Progress: worker w owns tiles w, w + n_workers, ... and the whole grid (workers and servers) is
+// resident at once: the launcher sizes it from the occupancy query.  A worker publishes a tile's
+// count before it ever waits for that tile's prefix, and waits only for tiles it has published;
+// a server waits for counts of its current block and for earlier blocks.  So every wait is for
+// something a running wave produces without waiting on the waiter.  Waits are bounded anyway:
+// after ROSE_SPIN_LIMIT failed polls, or once the abort flag is set, a wave stops waiting, sets
+// the flag, and the launch is reported as failed; every wave always reaches the end of the kernel.
 // ---------------------------------------------------------------------------------------------
 constexpr u64 kStatusShift = 62;
 constexpr u64 kStatusAggregate = 1;   // tile word: the tile's count;  block word: the block's count
@@ -188,7 +207,8 @@ constexpr u64 kStatusPrefix = 2;      // tile word: the tile's exclusive prefix;
 constexpr u64 kValueMask = (1ull << kStatusShift) - 1;
 
 #ifndef ROSE_DIAG
-#define ROSE_DIAG 0           // timing experiments only: 1 skips the cross-tile prefix, 2 skips the bucket writes
+#define ROSE_DIAG 0           // timing experiments only: 1 no waiting for prefixes, 2 no bucket writes,
+                              // 4 no publishing, 8 no parking in LDS
 #endif
 #ifndef ROSE_SPIN_LIMIT
 #define ROSE_SPIN_LIMIT (1u << 22)   // failed polls after which a wave gives up and flags the launch
@@ -260,97 +280,237 @@ __device__ __forceinline__ bool block_look_back(u64 *block_desc, unsigned int *a
     return true;
 }
 
-// Exclusive prefix of `tile` (own count `total`) in its chain; executed by one whole wave.
-__device__ __forceinline__ bool tile_prefix(const EncodeArgs &a, int32_t tile, int32_t shard, uint32_t total,
-                                            int lane, u64 *out) {
-    const int32_t chain_first = a.chain_first[shard];
-    const int32_t chain_last = a.chain_first[shard + 1] - 1;
-    const int32_t rel = tile - chain_first;
-    const int32_t q = rel & (kBlock - 1);                       // position inside the block
-    const int32_t blk_first = a.block_first[shard];
-    const int32_t blk = blk_first + rel / kBlock;
-    unsigned int spins = 0;
-    if (q != kBlock - 1 && tile != chain_last) {
-        // ordinary tile: publish the count, wait for the leader's answer in the same word
-        if (lane == 0) desc_store(a.tile_desc + tile, (kStatusAggregate << kStatusShift) | total);
-        for (;;) {
-            u64 v = desc_load(a.tile_desc + tile);
-            if ((v >> kStatusShift) == kStatusPrefix) {
-                *out = v & kValueMask;
-                return true;
+// A serving wave: blocks server, server + n_servers, ... in increasing order.
+__device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server, int lane) {
+    int32_t shard = 0;
+    for (int32_t blk = server; blk < a.n_blocks; blk += a.n_servers) {
+        while (blk >= a.block_first[shard + 1]) ++shard;          // blocks are numbered chain by chain
+        const int32_t blk_first = a.block_first[shard];
+        const int32_t first_tile = a.chain_first[shard] + (blk - blk_first) * kBlock;
+        const int32_t n = min(kBlock, a.chain_first[shard + 1] - first_tile);   // tiles in this block
+        unsigned int spins = 0;
+        bool ok = true;
+        u64 agg = 0;
+        for (;;) {   // lane i takes the count of the block's tile i
+            u64 v = (lane < n) ? desc_load(a.tile_desc + first_tile + lane) : (kStatusAggregate << kStatusShift);
+            if (__ballot((v >> kStatusShift) == 0) == 0) {
+                agg = v & kValueMask;
+                break;
             }
-            if (!keep_waiting(a.abort_flag, spins, lane)) return false;
+            if (!keep_waiting(a.abort_flag, spins, lane)) {
+                ok = false;
+                break;
+            }
         }
-    }
-    // leader: lane i < q takes the aggregate of the block's tile i, lane q this tile's own count
-    u64 agg;
-    for (;;) {
-        u64 v = (lane < q) ? desc_load(a.tile_desc + (tile - q + lane)) : ((kStatusAggregate << kStatusShift) | 0);
-        if (__ballot((v >> kStatusShift) == 0) == 0) {
-            agg = (lane < q) ? (v & kValueMask) : (lane == q ? (u64)total : 0);
-            break;
+        const uint32_t incl = wave_incl_scan((uint32_t)agg);    // <= 64 tiles * kTile entries
+        const uint32_t block_total = __shfl(incl, 63, 64);
+        u64 block_excl = 0;
+        if (ok && blk > blk_first) {
+            if (lane == 0) desc_store(a.block_desc + blk, (kStatusAggregate << kStatusShift) | block_total);
+            ok = block_look_back(a.block_desc, a.abort_flag, blk, blk_first, lane, &block_excl);
         }
-        if (!keep_waiting(a.abort_flag, spins, lane)) return false;
+        // published even after giving up, so that nobody keeps waiting on this block
+        if (lane == 0) desc_store(a.block_desc + blk, (kStatusPrefix << kStatusShift) | (block_excl + block_total));
+        if (lane < n)
+            desc_store(a.tile_desc + first_tile + lane,
+                       (kStatusPrefix << kStatusShift) | (block_excl + (incl - (uint32_t)agg)));
     }
-    const uint32_t incl = wave_incl_scan((uint32_t)agg);        // <= 64 tiles * kTile entries
-    const uint32_t block_total = __shfl(incl, 63, 64);
-    u64 block_excl = 0;
-    bool ok = true;
-    if (blk > blk_first) {
-        if (lane == 0) desc_store(a.block_desc + blk, (kStatusAggregate << kStatusShift) | block_total);
-        ok = block_look_back(a.block_desc, a.abort_flag, blk, blk_first, lane, &block_excl);
-    }
-    // published even after giving up, so that nobody keeps waiting on this block
-    if (lane == 0) desc_store(a.block_desc + blk, (kStatusPrefix << kStatusShift) | (block_excl + block_total));
-    const u64 excl = block_excl + (incl - (uint32_t)agg);
-    if (lane < q) desc_store(a.tile_desc + (tile - q + lane), (kStatusPrefix << kStatusShift) | excl);
-    *out = __shfl(excl, q, 64);
-    return ok;
 }
 
 // ---------------------------------------------------------------------------------------------
-// encode: persistent workgroups walk the tiles: workgroup w takes tiles w, w + grid, ...
-// Per tile:
-//   1. issue all 128-bit loads of the tile (old and new), 2. XOR -> 8-bit change mask per vector,
-//   3. wave prefix sums of the popcounts, wave totals through LDS, 4. wave 0 obtains the tile's
-//   exclusive prefix in its chain (see above), 5. every lane writes its changed
-//   (local index, new pattern) pairs at bucket position prefix + rank.
+// encode: persistent workgroups.  Workgroups 0 .. n_workers-1 walk the tiles (worker w takes tiles
+// w, w + n_workers, ...), the remaining ones serve prefixes (above).
+//
+// Worker, per tile: (1) the tile's 128-bit loads were issued one tile earlier; XOR old and new
+// into an 8-bit change mask per vector, (2) issue the NEXT tile's loads, (3) wave prefix sums of
+// the popcounts, wave totals through LDS, (4) publish the tile's count, (5) park the tile's
+// entries, compacted, in an LDS ring and go on.  The wait for a tile's prefix is deferred: only
+// when the ring (kRing entries) or the queue of parked tiles (kQueue) is full, and at the end, are
+// the parked tiles' prefixes collected (one lane per parked tile, all polled together) and their
+// entries copied to the buckets with contiguous stores.  This keeps loads in flight while counts
+// travel between workgroups.  A tile with more than kRing entries is written straight from
+// registers after a drain.
 // Inside a tile wave w covers a contiguous part and walks it in kIters steps of 512 elements,
 // so the order (wave, step, lane, element) is ascending local index.
 // ---------------------------------------------------------------------------------------------
+#ifndef ROSE_RING
+#define ROSE_RING 4096
+#endif
+#ifndef ROSE_QUEUE
+#define ROSE_QUEUE 8
+#endif
+constexpr int kRing = ROSE_RING;        // entries parked per workgroup (power of two)
+constexpr int kQueue = ROSE_QUEUE;      // tiles parked per workgroup (<= 64)
+constexpr u64 kUnknown = ~0ull;
+static_assert((kRing & (kRing - 1)) == 0 && (kQueue & (kQueue - 1)) == 0 && kQueue <= 64,
+              "ring and queue sizes must be powers of two, the queue at most a wave");
+
+enum : int { kLoadVec = 0, kLoadGeneral = 1 };
+
+struct TileCtx {
+    Piece pc;
+    const uint16_t *old_base;
+    const void *new_base;
+    uint32_t k_tile;
+    uint32_t limit;     // see load_raw
+    uint32_t vec;       // 128-bit loads are legal for this tile
+    uint32_t pad;       // no padding bytes: the struct is copied between registers only
+};
+
+__device__ __forceinline__ TileCtx tile_ctx(const EncodeArgs &a, int32_t tile) {
+    TileCtx c;
+    c.pc = load_piece(a.pieces + cload32(a.tile_piece + tile));
+    c.old_base = reinterpret_cast<const uint16_t *>(cload64(a.old_ptrs + c.pc.tensor));
+    c.new_base = reinterpret_cast<const void *>(cload64(a.new_ptrs + c.pc.tensor));
+    c.k_tile = (uint32_t)(tile - c.pc.first_tile) * (uint32_t)kTile;
+    c.limit = (c.k_tile + (uint32_t)kTile <= (uint32_t)c.pc.len) ? 0xFFFFFFFFu : (uint32_t)c.pc.len;
+    // uniform choice: aligned piece and aligned tensors -> 128-bit loads
+    c.vec = ((c.pc.flags & kPieceVec) && ((((uintptr_t)c.old_base) | ((uintptr_t)c.new_base)) & 15u) == 0) ? 1u : 0u;
+    c.pad = 0;
+    return c;
+}
+
 template <int NEW_F32>
 __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
-    __shared__ uint32_t s_wave_total[kWaves];
-    __shared__ u64 s_excl;
-    __shared__ int32_t s_ok;
+    __shared__ uint32_t s_ring_idx[kRing];
+    __shared__ uint16_t s_ring_val[kRing];
+    __shared__ uint32_t s_wave_total[2][kWaves];
+    __shared__ u64 s_q_excl[kQueue];        // exclusive prefix of a parked tile once collected
+    __shared__ int32_t s_q_tile[kQueue];
+    __shared__ uint32_t s_q_count[kQueue];
+    __shared__ uint32_t s_q_off[kQueue];
+    __shared__ int32_t s_q_shard[kQueue];
+    __shared__ int32_t s_q_seg[kQueue];     // tensor whose segment starts with this tile, else -1
+    __shared__ int32_t s_q_last[kQueue];    // 1 if the tile is the last of its chain
+    __shared__ int32_t s_ok, s_ready;
+    __shared__ u64 s_direct_excl;
+
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if ((int32_t)blockIdx.x >= a.n_workers) {
+        serve_blocks(a, ((int32_t)blockIdx.x - a.n_workers) * kWaves + __builtin_amdgcn_readfirstlane(wave), lane);
+        return;
+    }
 
-    for (int32_t tile = (int32_t)blockIdx.x; tile < a.n_tiles; tile += (int32_t)gridDim.x) {
-        const Piece pc = load_piece(a.pieces + cload32(a.tile_piece + tile));
-        const uint16_t *old_base = reinterpret_cast<const uint16_t *>(cload64(a.old_ptrs + pc.tensor));
-        const void *new_base = reinterpret_cast<const void *>(cload64(a.new_ptrs + pc.tensor));
-        const uint32_t k_tile = (uint32_t)(tile - pc.first_tile) * (uint32_t)kTile;
-        const uint32_t k_wave = k_tile + (uint32_t)wave * kWaveSpan;
-        // uniform choice: full, aligned tile -> straight 128-bit loads
-        const bool fast = (pc.flags & kPieceVec) && k_tile + (uint32_t)kTile <= (uint32_t)pc.len &&
-                          ((((uintptr_t)old_base) | ((uintptr_t)new_base)) & 15u) == 0;
+    // uniform bookkeeping, kept identical in every thread; the queue is a circular FIFO whose
+    // i-th oldest tile sits in slot (q_head + i) mod kQueue, the ring holds their entries in order
+    int q_head = 0, q_len = 0;
+    uint32_t ring_used = 0, ring_head = 0;
+    int parity = 0;
 
+    // Copy parked tiles whose prefixes have arrived to the buckets, oldest first.  With all = false
+    // it waits for the oldest tile only and takes along every following tile that is ready too;
+    // with all = true it waits for every parked tile.
+    auto drain = [&](bool all) {
+        __syncthreads();                               // parked entries and queue words are visible
+        if (wave == 0) {
+            bool ok = true;
+            const int slot = (q_head + lane) & (kQueue - 1);
+            u64 e = (lane < q_len) ? kUnknown : 0;
+            int n_ready = q_len;
+#if !(ROSE_DIAG & 1)
+            unsigned int spins = 0;
+            const int32_t my_tile = (lane < q_len) ? s_q_tile[slot] : 0;
+            for (;;) {
+                if (e == kUnknown) {
+                    u64 v = desc_load(a.tile_desc + my_tile);
+                    if ((v >> kStatusShift) == kStatusPrefix) e = v & kValueMask;
+                }
+                const u64 unknown = __ballot(e == kUnknown);
+                n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
+                if (all ? (n_ready == q_len) : (n_ready >= 1)) break;
+                if (!keep_waiting(a.abort_flag, spins, lane)) {
+                    ok = false;         // give up: drop everything that is parked
+                    n_ready = q_len;
+                    break;
+                }
+            }
+#else
+            e = 0;
+#endif
+            if (lane < n_ready) s_q_excl[slot] = e;
+            if (lane == 0) {
+                s_ok = ok ? 1 : 0;
+                s_ready = n_ready;
+            }
+        }
+        __syncthreads();
+        const int n_ready = s_ready;
+        uint32_t freed = 0;
+        for (int i = 0; i < n_ready; ++i) {
+            const int slot = (q_head + i) & (kQueue - 1);
+            const uint32_t cnt = s_q_count[slot];
+            freed += cnt;
+            if (s_ok && !(ROSE_DIAG & 2)) {
+                const u64 excl = s_q_excl[slot];
+                const uint32_t off = s_q_off[slot];
+                const BucketDev b = a.bucket[s_q_shard[slot]];
+                if (threadIdx.x == 0) {
+                    if (s_q_seg[slot] >= 0) b.seg_off[s_q_seg[slot]] = (int64_t)excl;
+                    if (s_q_last[slot]) b.seg_off[a.n_tensors] = (int64_t)(excl + cnt);
+                }
+                for (uint32_t k = threadIdx.x; k < cnt; k += kThreads) {
+                    const u64 pos = excl + k;
+                    if (pos < (u64)b.capacity) {
+                        b.idx[pos] = (int32_t)s_ring_idx[(off + k) & (kRing - 1)];
+                        b.val[pos] = s_ring_val[(off + k) & (kRing - 1)];
+                    }
+                }
+            }
+        }
+        __syncthreads();                               // ring and queue slots may be reused
+        q_head = (q_head + n_ready) & (kQueue - 1);
+        q_len -= n_ready;
+        ring_used -= freed;
+    };
+
+    int32_t tile = (int32_t)blockIdx.x;
+    if (tile >= a.n_tiles) return;
+    TileCtx cur = tile_ctx(a, tile);
+    RawTile<0> raw_old;
+    RawTile<NEW_F32> raw_new;
+    if (cur.vec) {
+        const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
+        load_raw(cur.old_base, cur.pc, k_wave, lane, cur.limit, raw_old);
+        load_raw(cur.new_base, cur.pc, k_wave, lane, cur.limit, raw_new);
+    }
+
+    for (;;) {
+        const Piece pc = cur.pc;
+        const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
         uint4 nv[kIters];
         uint32_t mask[kIters];
-        if (fast) {
-            uint4 ov[kIters];
-            load_tile_fast<0>(old_base, pc, k_wave, lane, ov);
-            load_tile_fast<NEW_F32>(new_base, pc, k_wave, lane, nv);
+        if (cur.vec) {
 #pragma unroll
-            for (int j = 0; j < kIters; ++j) mask[j] = nz16_mask(xor4(ov[j], nv[j]));
+            for (int j = 0; j < kIters; ++j) {
+                nv[j] = raw_to_bf16(raw_new, j);
+                mask[j] = nz16_mask(xor4(raw_old.v[j], nv[j]));
+            }
+            // a piece whose length is not a multiple of 8: the one vector that straddles its end
+            if (cur.limit != 0xFFFFFFFFu && (cur.limit & (kVec - 1))) {
+                const uint32_t ks = cur.limit & ~(uint32_t)(kVec - 1);
+                if (ks >= k_wave && ks < k_wave + (uint32_t)kWaveSpan && ((ks - k_wave) / kVec) % 64 == (uint32_t)lane) {
+                    const uint32_t js = (ks - k_wave) / (64 * kVec);
+                    uint4 o = load_vec_general<0>(cur.old_base, pc, ks);
+                    uint4 n = load_vec_general<NEW_F32>(cur.new_base, pc, ks);
+                    uint32_t m = nz16_mask(xor4(o, n));
+#pragma unroll
+                    for (int jj = 0; jj < kIters; ++jj) {
+                        if ((uint32_t)jj == js) {
+                            nv[jj] = n;
+                            mask[jj] = m;
+                        }
+                    }
+                }
+            }
         } else {
-            // kept as a rolled loop (one vector in flight) so that this rare path does not set
-            // the kernel's register budget; the selects put the result into static slots
+            // shapes or pointers that are not multiples of 16 bytes.  Kept as a rolled loop (one
+            // vector in flight) so that this rare path does not set the kernel's register budget;
+            // the selects put the result into static slots
 #pragma unroll 1
             for (int j = 0; j < kIters; ++j) {
                 uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
-                uint4 o = load_vec_general<0>(old_base, pc, k);
-                uint4 n = load_vec_general<NEW_F32>(new_base, pc, k);
+                uint4 o = load_vec_general<0>(cur.old_base, pc, k);
+                uint4 n = load_vec_general<NEW_F32>(cur.new_base, pc, k);
                 uint32_t m = nz16_mask(xor4(o, n));
 #pragma unroll
                 for (int jj = 0; jj < kIters; ++jj) {
@@ -359,6 +519,19 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
                         mask[jj] = m;
                     }
                 }
+            }
+        }
+
+        // the next tile's loads go out now and stay in flight during everything below
+        const int32_t next = tile + a.n_workers;
+        const bool has_next = next < a.n_tiles;
+        TileCtx nxt = cur;
+        if (has_next) {
+            nxt = tile_ctx(a, next);
+            if (nxt.vec) {
+                const uint32_t kw = nxt.k_tile + (uint32_t)wave * kWaveSpan;
+                load_raw(nxt.old_base, nxt.pc, kw, lane, nxt.limit, raw_old);
+                load_raw(nxt.new_base, nxt.pc, kw, lane, nxt.limit, raw_new);
             }
         }
 
@@ -372,59 +545,115 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             rank[j] = wave_total + inc - c;
             wave_total += __shfl(inc, 63, 64);
         }
-        if (lane == 0) s_wave_total[wave] = wave_total;
+        if (lane == 0) s_wave_total[parity][wave] = wave_total;
         __syncthreads();
-
         uint32_t wave_excl = 0, tile_total = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            uint32_t c = s_wave_total[w];
+            uint32_t c = s_wave_total[parity][w];
             if (w < wave) wave_excl += c;
             tile_total += c;
         }
+        parity ^= 1;
 
-        if (wave == 0) {
-            u64 excl = 0;
-            bool ok = true;
-#if !(ROSE_DIAG & 1)
-            ok = tile_prefix(a, tile, pc.shard, tile_total, lane, &excl);
-#endif
-            if (lane == 0) {
-                s_excl = excl;
-                s_ok = ok ? 1 : 0;
-            }
-        }
-        __syncthreads();
-        const u64 tile_excl = s_excl;
-        const bool ok = s_ok != 0;
+        // publish the count: a serving wave turns it into this tile's prefix
+        if (threadIdx.x == 0 && !(ROSE_DIAG & 4))
+            desc_store(a.tile_desc + tile, (kStatusAggregate << kStatusShift) | tile_total);
 
-        const BucketDev b = a.bucket[pc.shard];
-        if (threadIdx.x == 0 && ok) {
-            if ((pc.flags & kPieceFirst) && tile == pc.first_tile) b.seg_off[pc.tensor] = (int64_t)tile_excl;
-            if (tile == a.chain_first[pc.shard + 1] - 1) b.seg_off[a.n_tensors] = (int64_t)(tile_excl + tile_total);
+        const bool big = tile_total > (uint32_t)kRing;
+        if (big) {
+            if (q_len > 0) drain(true);
+        } else {
+            while (q_len == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
         }
 
-        if (ok && !(ROSE_DIAG & 2)) {
-            const u64 wave_base = tile_excl + wave_excl;
+        const int32_t chain_last = a.chain_first[pc.shard + 1] - 1;
+        const int32_t seg = ((pc.flags & kPieceFirst) && tile == pc.first_tile) ? pc.tensor : -1;
+        if (!big) {
+            // park the entries: ring slot = ring_head + rank inside the tile
+            const uint32_t base = ring_head + wave_excl;
 #pragma unroll
             for (int j = 0; j < kIters; ++j) {
                 uint32_t m = mask[j];
-                u64 pos = wave_base + rank[j];
-                uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
-                while (m) {
-                    uint32_t e = __ffs(m) - 1;
+                uint32_t slot = base + rank[j];
+                const uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
+                while (m && !(ROSE_DIAG & 8)) {
+                    const uint32_t e = __ffs(m) - 1;
                     m &= m - 1;
-                    if (pos < (u64)b.capacity) {
-                        b.idx[pos] = (int32_t)(local0 + e);
-                        b.val[pos] = (uint16_t)pick16(nv[j], e);
-                    }
-                    ++pos;
+                    s_ring_idx[slot & (kRing - 1)] = local0 + e;
+                    s_ring_val[slot & (kRing - 1)] = (uint16_t)pick16(nv[j], e);
+                    ++slot;
                 }
             }
+            if (threadIdx.x == 0) {
+                const int slot = (q_head + q_len) & (kQueue - 1);
+                s_q_tile[slot] = tile;
+                s_q_count[slot] = tile_total;
+                s_q_off[slot] = ring_head;
+                s_q_shard[slot] = pc.shard;
+                s_q_seg[slot] = seg;
+                s_q_last[slot] = tile == chain_last;
+            }
+            ++q_len;
+            ring_used += tile_total;
+            ring_head = (ring_head + tile_total) & (kRing - 1);
+        } else {
+            // more entries than the ring holds: wait for the prefix now, write from registers
+            if (wave == 0) {
+                bool ok = true;
+                u64 excl = 0;
+#if !(ROSE_DIAG & 1)
+                unsigned int spins = 0;
+                for (;;) {
+                    u64 v = desc_load(a.tile_desc + tile);
+                    if ((v >> kStatusShift) == kStatusPrefix) {
+                        excl = v & kValueMask;
+                        break;
+                    }
+                    if (!keep_waiting(a.abort_flag, spins, lane)) {
+                        ok = false;
+                        break;
+                    }
+                }
+#endif
+                if (lane == 0) {
+                    s_direct_excl = excl;
+                    s_ok = ok ? 1 : 0;
+                }
+            }
+            __syncthreads();
+            const u64 tile_excl = s_direct_excl;
+            const BucketDev b = a.bucket[pc.shard];
+            if (s_ok && !(ROSE_DIAG & 2)) {
+                if (threadIdx.x == 0) {
+                    if (seg >= 0) b.seg_off[seg] = (int64_t)tile_excl;
+                    if (tile == chain_last) b.seg_off[a.n_tensors] = (int64_t)(tile_excl + tile_total);
+                }
+                const u64 wave_base = tile_excl + wave_excl;
+#pragma unroll
+                for (int j = 0; j < kIters; ++j) {
+                    uint32_t m = mask[j];
+                    u64 pos = wave_base + rank[j];
+                    const uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
+                    while (m) {
+                        const uint32_t e = __ffs(m) - 1;
+                        m &= m - 1;
+                        if (pos < (u64)b.capacity) {
+                            b.idx[pos] = (int32_t)(local0 + e);
+                            b.val[pos] = (uint16_t)pick16(nv[j], e);
+                        }
+                        ++pos;
+                    }
+                }
+            }
+            __syncthreads();                           // s_direct_excl / s_ok are reused
         }
-        // No barrier is needed before the shared words are reused: each is written only after a
-        // barrier that every wave reaches after its last read of the previous value.
+
+        if (!has_next) break;
+        cur = nxt;
+        tile = next;
     }
+    if (q_len > 0) drain(true);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -566,7 +795,8 @@ __global__ __launch_bounds__(256) void bw_read_kernel(const uint4 *src, size_t n
 #define ROSE_WGS_PER_CU 8
 #endif
 
-static int encode_grid(int new_is_f32, int32_t n_tiles, int *grid) {
+// Number of workgroups that fit on the device at once for the encode kernel.
+static int encode_resident(int new_is_f32, int *resident) {
     static int cached[2] = {0, 0};          // per kernel variant; the device set is homogeneous
     if (!cached[new_is_f32]) {
         int dev = 0, cus = 0, per_cu = 0;
@@ -580,25 +810,40 @@ static int encode_grid(int new_is_f32, int32_t n_tiles, int *grid) {
         if (per_cu > ROSE_WGS_PER_CU) per_cu = ROSE_WGS_PER_CU;
         cached[new_is_f32] = cus * per_cu;
     }
-    *grid = cached[new_is_f32] < n_tiles ? cached[new_is_f32] : n_tiles;
+    *resident = cached[new_is_f32];
     return 0;
 }
 
-int launch_encode(const EncodeArgs &a, int new_is_f32, void *stream) {
+#ifndef ROSE_SERVER_WGS
+#define ROSE_SERVER_WGS 16          // workgroups of the grid that serve prefixes (kWaves servers each)
+#endif
+
+int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int grid = 0;
-    int rc = encode_grid(new_is_f32, a.n_tiles, &grid);
+    EncodeArgs a = args;
+    int resident = 0;
+    int rc = encode_resident(new_is_f32, &resident);
     if (rc) return rc;
-    int reset_blocks = (a.n_tiles + 1023) / 1024;
+    // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
+    // a quarter of what is resident
+    int server_wgs = (a.n_blocks + kWaves - 1) / kWaves;
+    if (server_wgs > ROSE_SERVER_WGS) server_wgs = ROSE_SERVER_WGS;
+    if (server_wgs > resident / 4) server_wgs = resident / 4;
+    if (server_wgs < 1) server_wgs = 1;
+    int workers = resident - server_wgs;
+    if (workers < 1) return (int)hipErrorInvalidValue;       // a device that holds one workgroup only
+    if (workers > a.n_tiles) workers = a.n_tiles;
+    a.n_workers = workers;
+    a.n_servers = server_wgs * kWaves;
+    const int64_t n_desc = (int64_t)a.n_tiles + a.n_blocks;  // tile and block words are one array
+    int reset_blocks = (int)((n_desc + 1023) / 1024);
     if (reset_blocks < 1) reset_blocks = 1;
     if (reset_blocks > 2048) reset_blocks = 2048;
-    // tile and block descriptors are one contiguous array
-    hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, a.tile_desc, a.abort_flag,
-                       (int64_t)a.n_tiles + a.n_blocks);
+    hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, a.tile_desc, a.abort_flag, n_desc);
     if (new_is_f32)
-        hipLaunchKernelGGL(encode_kernel<1>, dim3(grid), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL(encode_kernel<1>, dim3(workers + server_wgs), dim3(kThreads), 0, st, a);
     else
-        hipLaunchKernelGGL(encode_kernel<0>, dim3(grid), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL(encode_kernel<0>, dim3(workers + server_wgs), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, st, a);
     return (int)hipGetLastError();
 }

@@ -74,10 +74,12 @@ struct EncodeArgs {
     int32_t n_blocks;
     int32_t n_tensors;
     int32_t tp;
+    int32_t n_workers;                      // workgroups that walk tiles; the rest of the grid serves prefixes
+    int32_t n_servers;                      // waves that serve prefixes (kWaves per serving workgroup)
 };
 
-// Tiles of one chain are grouped in blocks of kBlock; the last tile of a block gathers the
-// block's counts and hands every tile of the block its prefix.
+// Tiles of one chain are grouped in blocks of kBlock; a serving wave gathers a block's counts
+// and hands every tile of the block its prefix.
 constexpr int kBlock = 64;
 
 // workspace layout (bytes): header, tile descriptors, block descriptors
