@@ -85,6 +85,7 @@ extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *
     a.new_ptrs = new_ptrs;
     char *ws = static_cast<char *>(workspace);
     a.abort_flag = reinterpret_cast<unsigned int *>(ws + rose::kWsAbortOff);
+    a.ticket = reinterpret_cast<unsigned int *>(ws + rose::kWsTicketOff);
     a.tile_desc = reinterpret_cast<unsigned long long *>(ws + rose::kWsHeaderBytes);
     a.n_tiles = (int32_t)p->tile_piece.size();
     a.n_blocks = p->block_first[p->tp];

@@ -221,10 +221,11 @@ __device__ __forceinline__ u64 desc_load(u64 *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__global__ void reset_kernel(u64 *desc, unsigned int *abort_flag, int64_t n_desc) {
+// The workspace is one array of 64-bit words: header (abort flag, ticket counters), tile words,
+// block words.  All of it starts at zero.
+__global__ void reset_kernel(u64 *workspace, int64_t n_words) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *abort_flag = 0;
-    for (; i < n_desc; i += (int64_t)gridDim.x * blockDim.x) desc[i] = 0;
+    for (; i < n_words; i += (int64_t)gridDim.x * blockDim.x) workspace[i] = 0;
 }
 
 // After encode: if any wave gave up waiting, mark every bucket as invalid (total = -1) so that
@@ -232,6 +233,15 @@ __global__ void reset_kernel(u64 *desc, unsigned int *abort_flag, int64_t n_desc
 __global__ void finalize_kernel(EncodeArgs a) {
     if (threadIdx.x < (unsigned)a.tp && *a.abort_flag) a.bucket[threadIdx.x].seg_off[a.n_tensors] = -1;
 }
+
+#ifndef ROSE_STATS
+#define ROSE_STATS 0          // experiments only: count polls into the workspace header
+#endif
+#if ROSE_STATS
+#define STAT_ADD(a, i, v) atomicAdd(reinterpret_cast<unsigned long long *>(a.abort_flag) + 8 + (i), (unsigned long long)(v))
+#else
+#define STAT_ADD(a, i, v) ((void)0)
+#endif
 
 // bounded wait bookkeeping; returns false when the wave must stop waiting
 __device__ __forceinline__ bool keep_waiting(unsigned int *abort_flag, unsigned int &spins, int lane) {
@@ -302,6 +312,7 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
                 break;
             }
         }
+        if (lane == 0) { STAT_ADD(a, 0, 1); STAT_ADD(a, 1, spins); }
         const uint32_t incl = wave_incl_scan((uint32_t)agg);    // <= 64 tiles * kTile entries
         const uint32_t block_total = __shfl(incl, 63, 64);
         u64 block_excl = 0;
@@ -370,6 +381,67 @@ __device__ __forceinline__ TileCtx tile_ctx(const EncodeArgs &a, int32_t tile) {
     return c;
 }
 
+// Tile at position (ticket mod kBlock) of block (ticket / kBlock) * kBatch + j, or -1 if that block
+// does not exist or is a chain's short last block without that position.  Uniform.
+__device__ __forceinline__ int32_t ticket_tile(const EncodeArgs &a, int32_t ticket, int32_t j) {
+    const int32_t blk = (ticket / kBlock) * kBatch + j;
+    if (blk >= a.n_blocks) return -1;
+    int32_t shard = 0;
+    while (blk >= a.block_first[shard + 1]) ++shard;
+    const int32_t t = a.chain_first[shard] + (blk - a.block_first[shard]) * kBlock + (ticket & (kBlock - 1));
+    return t < a.chain_first[shard + 1] ? t : -1;
+}
+
+// A worker's position in the tile order it is given by its tickets (uniform state).
+struct Walk {
+    int32_t ticket, j;          // current ticket and batch slot
+    int32_t next_ticket;        // ticket fetched ahead of time
+    bool have_next;
+    uint32_t rr;                // ticket counter to ask next (round robin)
+    uint32_t lanes_done;        // counters that have run out
+};
+enum : int { kWalkTile = 0, kWalkNeedTicket = 1, kWalkDone = 2 };
+constexpr uint32_t kAllLanes = kTicketLanes == 32 ? 0xFFFFFFFFu : ((1u << kTicketLanes) - 1u);
+
+// counter the next request goes to (only called while some counter is left)
+__device__ __forceinline__ uint32_t walk_pick_lane(Walk &w) {
+    while (w.lanes_done & (1u << w.rr)) w.rr = (w.rr + 1) % kTicketLanes;
+    const uint32_t c = w.rr;
+    w.rr = (w.rr + 1) % kTicketLanes;
+    return c;
+}
+
+// take in the answer n of counter c: local ticket n of counter c is ticket n mod kBlock of group
+// (n / kBlock) * kTicketLanes + c
+__device__ __forceinline__ void walk_accept(const EncodeArgs &a, Walk &w, uint32_t c, uint32_t n) {
+    if (n >= (uint32_t)a.lane_tickets) {
+        w.lanes_done |= 1u << c;
+    } else {
+        w.next_ticket = (int32_t)(((n / kBlock) * kTicketLanes + c) * kBlock + (n & (kBlock - 1)));
+        w.have_next = true;
+    }
+}
+
+// Advance to the next tile.  kWalkNeedTicket: the current ticket is used up and no further one
+// is at hand (ask a counter, then call again); kWalkDone: no tiles are left.
+__device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *tile) {
+    for (;;) {
+        while (w.j + 1 < kBatch) {
+            ++w.j;
+            const int32_t t = ticket_tile(a, w.ticket, w.j);
+            if (t >= 0) {
+                *tile = t;
+                return kWalkTile;
+            }
+        }
+        w.j = kBatch;
+        if (!w.have_next) return w.lanes_done == kAllLanes ? kWalkDone : kWalkNeedTicket;
+        w.ticket = w.next_ticket;
+        w.have_next = false;
+        w.j = -1;
+    }
+}
+
 template <int NEW_F32>
 __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
     __shared__ uint32_t s_ring_idx[kRing];
@@ -383,11 +455,12 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
     __shared__ int32_t s_q_seg[kQueue];     // tensor whose segment starts with this tile, else -1
     __shared__ int32_t s_q_last[kQueue];    // 1 if the tile is the last of its chain
     __shared__ int32_t s_ok, s_ready;
+    __shared__ int32_t s_ticket[2], s_ticket_sync;
     __shared__ u64 s_direct_excl;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if ((int32_t)blockIdx.x >= a.n_workers) {
-        serve_blocks(a, ((int32_t)blockIdx.x - a.n_workers) * kWaves + __builtin_amdgcn_readfirstlane(wave), lane);
+    if ((int32_t)blockIdx.x < a.n_server_wgs) {
+        serve_blocks(a, (int32_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wave), lane);
         return;
     }
 
@@ -431,6 +504,9 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             if (lane == 0) {
                 s_ok = ok ? 1 : 0;
                 s_ready = n_ready;
+#if !(ROSE_DIAG & 1)
+                STAT_ADD(a, 2, 1); STAT_ADD(a, 3, spins); STAT_ADD(a, 4, n_ready); STAT_ADD(a, 5, q_len);
+#endif
             }
         }
         __syncthreads();
@@ -463,8 +539,33 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
         ring_used -= freed;
     };
 
-    int32_t tile = (int32_t)blockIdx.x;
-    if (tile >= a.n_tiles) return;
+    // Tiles come from tickets (dynamic, so that faster workgroups take more): a ticket is fetched
+    // one batch ahead by thread 0 and handed to the others through LDS at the next barrier.
+    auto fetch_ticket = [&](uint32_t c) -> unsigned int {
+        return __hip_atomic_fetch_add(a.ticket + c * (kTicketStride / sizeof(unsigned int)), 1u, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+    };
+    Walk walk;
+    walk.ticket = 0;
+    walk.j = kBatch;
+    walk.have_next = false;
+    walk.next_ticket = 0;
+    walk.rr = blockIdx.x % kTicketLanes;
+    walk.lanes_done = 0;
+    auto fetch_ticket_now = [&]() {        // all threads; two barriers; needs a counter that is left
+        const uint32_t c = walk_pick_lane(walk);
+        if (threadIdx.x == 0) s_ticket_sync = (int32_t)fetch_ticket(c);
+        __syncthreads();
+        walk_accept(a, walk, c, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket_sync));
+        __syncthreads();
+    };
+    int32_t tile = -1;
+    for (;;) {
+        const int st = walk_step(a, walk, &tile);
+        if (st == kWalkTile) break;
+        if (st == kWalkDone) return;
+        fetch_ticket_now();
+    }
     TileCtx cur = tile_ctx(a, tile);
     RawTile<0> raw_old;
     RawTile<NEW_F32> raw_new;
@@ -475,6 +576,15 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
     }
 
     for (;;) {
+        // ask for the next ticket as soon as the one fetched ahead has been taken into use
+        const bool request = !walk.have_next && walk.lanes_done != kAllLanes;
+        uint32_t request_lane = 0;
+        unsigned int pending_ticket = 0;
+        if (request) {
+            request_lane = walk_pick_lane(walk);
+            if (threadIdx.x == 0) pending_ticket = fetch_ticket(request_lane);
+        }
+
         const Piece pc = cur.pc;
         const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
         uint4 nv[kIters];
@@ -523,10 +633,10 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
         }
 
         // the next tile's loads go out now and stay in flight during everything below
-        const int32_t next = tile + a.n_workers;
-        const bool has_next = next < a.n_tiles;
+        int32_t next = -1;
+        int next_state = walk_step(a, walk, &next);     // kWalkNeedTicket: decided after the barrier
         TileCtx nxt = cur;
-        if (has_next) {
+        if (next_state == kWalkTile) {
             nxt = tile_ctx(a, next);
             if (nxt.vec) {
                 const uint32_t kw = nxt.k_tile + (uint32_t)wave * kWaveSpan;
@@ -546,7 +656,9 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             wave_total += __shfl(inc, 63, 64);
         }
         if (lane == 0) s_wave_total[parity][wave] = wave_total;
+        if (request && threadIdx.x == 0) s_ticket[parity] = (int32_t)pending_ticket;
         __syncthreads();
+        if (request) walk_accept(a, walk, request_lane, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket[parity]));
         uint32_t wave_excl = 0, tile_total = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
@@ -649,7 +761,21 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             __syncthreads();                           // s_direct_excl / s_ok are reused
         }
 
-        if (!has_next) break;
+        // the rare case that the next tile could not be named before the barrier above: name it
+        // now and issue its loads late
+        while (next_state == kWalkNeedTicket) {
+            if (!walk.have_next && walk.lanes_done != kAllLanes) fetch_ticket_now();
+            next_state = walk_step(a, walk, &next);
+            if (next_state == kWalkTile) {
+                nxt = tile_ctx(a, next);
+                if (nxt.vec) {
+                    const uint32_t kw = nxt.k_tile + (uint32_t)wave * kWaveSpan;
+                    load_raw(nxt.old_base, nxt.pc, kw, lane, nxt.limit, raw_old);
+                    load_raw(nxt.new_base, nxt.pc, kw, lane, nxt.limit, raw_new);
+                }
+            }
+        }
+        if (next_state == kWalkDone) break;
         cur = nxt;
         tile = next;
     }
@@ -660,6 +786,9 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
 // apply: persistent grid over chunks of a bucket's entries; entries are in ascending local index
 // inside a segment, so neighbouring lanes store into the same or neighbouring lines.
 // ---------------------------------------------------------------------------------------------
+#ifndef ROSE_APPLY_RFO
+#define ROSE_APPLY_RFO 0
+#endif
 constexpr int kApplyPerLane = 4;
 constexpr int kApplyThreads = 256;
 constexpr int kApplyChunk = kApplyThreads * kApplyPerLane;
@@ -695,10 +824,12 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
         }
         uint16_t *dst = nullptr;
         bool have = false;
+        uint16_t *target[kApplyPerLane];
 #pragma unroll
         for (int i = 0; i < kApplyPerLane; ++i) {
+            target[i] = nullptr;
             int64_t ei = e + i;
-            if (ei >= total) break;
+            if (ei >= total) continue;
             while (ei >= seg_end) {
                 ++t;
                 seg_end = b.seg_off[t + 1];
@@ -708,8 +839,20 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
                 dst = static_cast<uint16_t *>(dst_ptrs[t]);
                 have = true;
             }
-            dst[ix[i]] = (uint16_t)vv[i];
+            target[i] = dst + ix[i];
         }
+#if ROSE_APPLY_RFO
+        // Read each target first: the line is then complete in L2 and leaves it as a full-line
+        // write instead of a byte-masked partial one.
+        uint32_t seen = 0;
+#pragma unroll
+        for (int i = 0; i < kApplyPerLane; ++i)
+            if (target[i]) seen += *target[i];
+        asm volatile("" ::"v"(seen));
+#endif
+#pragma unroll
+        for (int i = 0; i < kApplyPerLane; ++i)
+            if (target[i]) *target[i] = (uint16_t)vv[i];
     }
 }
 
@@ -825,21 +968,30 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
     int rc = encode_resident(new_is_f32, &resident);
     if (rc) return rc;
     // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
-    // a quarter of what is resident
+    // a quarter of what is resident.  They are the first workgroups of the grid, so they are
+    // resident before any worker waits for them.
     int server_wgs = (a.n_blocks + kWaves - 1) / kWaves;
     if (server_wgs > ROSE_SERVER_WGS) server_wgs = ROSE_SERVER_WGS;
     if (server_wgs > resident / 4) server_wgs = resident / 4;
     if (server_wgs < 1) server_wgs = 1;
     int workers = resident - server_wgs;
-    if (workers < 1) return (int)hipErrorInvalidValue;       // a device that holds one workgroup only
     if (workers > a.n_tiles) workers = a.n_tiles;
-    a.n_workers = workers;
+    // A worker that waits with a full queue relies on other workers to take the tickets that
+    // complete its blocks.  At most kTicketLanes groups of tickets are partly handed out at any
+    // time, so as long as the workers can park more tiles in total than those groups hold, some
+    // parked tile always belongs to a block whose tiles have all been taken.
+    if (workers < 1 ||
+        (workers < a.n_tiles && (int64_t)workers * kQueue <= (int64_t)kTicketLanes * kBlock * kBatch))
+        return (int)hipErrorInvalidValue;
+    a.n_server_wgs = server_wgs;
     a.n_servers = server_wgs * kWaves;
-    const int64_t n_desc = (int64_t)a.n_tiles + a.n_blocks;  // tile and block words are one array
-    int reset_blocks = (int)((n_desc + 1023) / 1024);
-    if (reset_blocks < 1) reset_blocks = 1;
+    const int32_t n_groups = (a.n_blocks + kBatch - 1) / kBatch;         // groups of kBlock tickets
+    a.lane_tickets = ((n_groups + kTicketLanes - 1) / kTicketLanes) * kBlock;
+    // header, tile words and block words are one array
+    const int64_t n_words = (int64_t)(kWsHeaderBytes / sizeof(u64)) + a.n_tiles + a.n_blocks;
+    int reset_blocks = (int)((n_words + 1023) / 1024);
     if (reset_blocks > 2048) reset_blocks = 2048;
-    hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, a.tile_desc, a.abort_flag, n_desc);
+    hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, reinterpret_cast<u64 *>(a.abort_flag), n_words);
     if (new_is_f32)
         hipLaunchKernelGGL(encode_kernel<1>, dim3(workers + server_wgs), dim3(kThreads), 0, st, a);
     else

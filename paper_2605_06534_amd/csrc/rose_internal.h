@@ -74,8 +74,11 @@ struct EncodeArgs {
     int32_t n_blocks;
     int32_t n_tensors;
     int32_t tp;
-    int32_t n_workers;                      // workgroups that walk tiles; the rest of the grid serves prefixes
+    int32_t n_server_wgs;                   // workgroups 0 .. n_server_wgs-1 serve prefixes, the rest walk tiles
     int32_t n_servers;                      // waves that serve prefixes (kWaves per serving workgroup)
+    int32_t lane_tickets;                   // tickets each ticket counter hands out
+    int32_t pad;
+    unsigned int *ticket;                   // workspace header: kTicketLanes counters, kTicketStride bytes apart
 };
 
 // Tiles of one chain are grouped in blocks of kBlock; a serving wave gathers a block's counts
@@ -83,8 +86,23 @@ struct EncodeArgs {
 constexpr int kBlock = 64;
 
 // workspace layout (bytes): header, tile descriptors, block descriptors
+// A ticket hands a worker kBatch tiles: the tiles at one position of kBatch consecutive blocks.
+// Tickets come from kTicketLanes counters, each serving every kTicketLanes-th group of kBlock
+// tickets, so that the atomics spread over several memory channels.
+#ifndef ROSE_BATCH
+#define ROSE_BATCH 1
+#endif
+#ifndef ROSE_TICKET_LANES
+#define ROSE_TICKET_LANES 16
+#endif
+constexpr int kBatch = ROSE_BATCH;
+constexpr int kTicketLanes = ROSE_TICKET_LANES;
+constexpr size_t kTicketStride = 4096;
+static_assert(kTicketLanes >= 1 && kTicketLanes <= 32, "ticket lanes are tracked in a 32-bit mask");
+
 constexpr size_t kWsAbortOff = 0;
-constexpr size_t kWsHeaderBytes = 256;
+constexpr size_t kWsTicketOff = kTicketStride;
+constexpr size_t kWsHeaderBytes = kTicketStride * (1 + kTicketLanes);
 
 struct CopyArgs {
     const Piece *pieces;
