@@ -27,18 +27,18 @@ __device__ __forceinline__ uint32_t pack_rne(uint32_t lo, uint32_t hi) {
     return (rne_bf16(lo) & 0xFFFFu) | (rne_bf16(hi) << 16);
 }
 
-// 8-bit mask of the 16-bit lanes of x that are non-zero (bit e = element e, little endian)
+// 8-bit mask of the 16-bit lanes of x that are non-zero (bit e = element e, little endian).
+// A packed 16-bit min with 1 turns the two halves of a dword into 0 / 1 (bits 0 and 16) in one
+// instruction; the four dwords are merged first (even elements in bits 0,2,4,6, odd ones in
+// 16,18,20,22) and the odd ones folded down at the end.
+__device__ __forceinline__ uint32_t nz16_pair(uint32_t x) {
+    uint32_t b;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(b) : "v"(x), "v"(0x00010001u));
+    return b;
+}
 __device__ __forceinline__ uint32_t nz16_mask(uint4 x) {
-    uint32_t m = 0;
-    m |= ((x.x & 0xFFFFu) != 0) ? 1u : 0u;
-    m |= ((x.x >> 16) != 0) ? 2u : 0u;
-    m |= ((x.y & 0xFFFFu) != 0) ? 4u : 0u;
-    m |= ((x.y >> 16) != 0) ? 8u : 0u;
-    m |= ((x.z & 0xFFFFu) != 0) ? 16u : 0u;
-    m |= ((x.z >> 16) != 0) ? 32u : 0u;
-    m |= ((x.w & 0xFFFFu) != 0) ? 64u : 0u;
-    m |= ((x.w >> 16) != 0) ? 128u : 0u;
-    return m;
+    const uint32_t t = nz16_pair(x.x) | (nz16_pair(x.y) << 2) | (nz16_pair(x.z) << 4) | (nz16_pair(x.w) << 6);
+    return (t | (t >> 15)) & 0xFFu;
 }
 
 // element e (0..7) of a vector of eight 16-bit patterns
@@ -47,14 +47,17 @@ __device__ __forceinline__ uint32_t pick16(uint4 v, uint32_t e) {
     return (e & 1u) ? (a >> 16) : (a & 0xFFFFu);
 }
 
-// inclusive prefix sum over the 64 lanes of a wave
+// inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS traffic): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then the row totals are broadcast into the following
+// rows (lane 15 of a row into the next row, lane 31 into the upper half).  A lane without a
+// source keeps the 0 passed as the old value.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
-    const int lane = __lane_id();
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-        uint32_t y = __shfl_up(x, s, 64);
-        if (lane >= s) x += y;
-    }
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
     return x;
 }
 
@@ -312,9 +315,8 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
                 break;
             }
         }
-        if (lane == 0) { STAT_ADD(a, 0, 1); STAT_ADD(a, 1, spins); }
         const uint32_t incl = wave_incl_scan((uint32_t)agg);    // <= 64 tiles * kTile entries
-        const uint32_t block_total = __shfl(incl, 63, 64);
+        const uint32_t block_total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
         u64 block_excl = 0;
         if (ok && blk > blk_first) {
             if (lane == 0) desc_store(a.block_desc + blk, (kStatusAggregate << kStatusShift) | block_total);
@@ -346,6 +348,9 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 // ---------------------------------------------------------------------------------------------
 #ifndef ROSE_RING
 #define ROSE_RING 4096
+#endif
+#ifndef ROSE_WAVES_PER_EU
+#define ROSE_WAVES_PER_EU 4     // register budget of the encode kernel: 512 / 4 = 128 VGPRs
 #endif
 #ifndef ROSE_QUEUE
 #define ROSE_QUEUE 8
@@ -443,12 +448,13 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
 }
 
 template <int NEW_F32>
-__global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
+__device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     __shared__ uint32_t s_ring_idx[kRing];
     __shared__ uint16_t s_ring_val[kRing];
     __shared__ uint32_t s_wave_total[2][kWaves];
-    __shared__ u64 s_q_excl[kQueue];        // exclusive prefix of a parked tile once collected
-    __shared__ int32_t s_q_tile[kQueue];
+    __shared__ u64 s_excl[2][kQueue];       // prefixes of the tiles an iteration copies out, oldest first
+    __shared__ u64 s_excl_sync[kQueue];     // the same for a blocking drain
+    __shared__ int32_t s_nready[2];
     __shared__ uint32_t s_q_count[kQueue];
     __shared__ uint32_t s_q_off[kQueue];
     __shared__ int32_t s_q_shard[kQueue];
@@ -464,60 +470,31 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
         return;
     }
 
-    // uniform bookkeeping, kept identical in every thread; the queue is a circular FIFO whose
-    // i-th oldest tile sits in slot (q_head + i) mod kQueue, the ring holds their entries in order
-    int q_head = 0, q_len = 0;
-    uint32_t ring_used = 0, ring_head = 0;
+    // Uniform bookkeeping, kept identical in every thread.  The queue is a circular FIFO whose i-th
+    // oldest tile sits in slot (q_head + i) mod kQueue; the ring holds their entries in that order.
+    // What one iteration copies out stays reserved ("held") until the next iteration's barrier,
+    // because slower threads may still be reading it.
+#if ROSE_STATS
+    unsigned long long st_iters = 0, st_drains = 0, st_spins = 0, st_async = 0, st_drain_clk = 0, st_clk0 = wall_clock64();
+#endif
+    int q_head = 0, q_len = 0, q_held = 0;
+    uint32_t ring_used = 0, ring_held = 0, ring_head = 0;
     int parity = 0;
+    // wave 0 only: lane i tracks the i-th oldest parked tile
+    int32_t wq_tile = 0;
+    u64 wq_e = kUnknown;        // its exclusive prefix once known
+    u64 polled = 0;             // answer of the poll issued at the end of the previous iteration
+    bool poll_out = false;
 
-    // Copy parked tiles whose prefixes have arrived to the buckets, oldest first.  With all = false
-    // it waits for the oldest tile only and takes along every following tile that is ready too;
-    // with all = true it waits for every parked tile.
-    auto drain = [&](bool all) {
-        __syncthreads();                               // parked entries and queue words are visible
-        if (wave == 0) {
-            bool ok = true;
-            const int slot = (q_head + lane) & (kQueue - 1);
-            u64 e = (lane < q_len) ? kUnknown : 0;
-            int n_ready = q_len;
-#if !(ROSE_DIAG & 1)
-            unsigned int spins = 0;
-            const int32_t my_tile = (lane < q_len) ? s_q_tile[slot] : 0;
-            for (;;) {
-                if (e == kUnknown) {
-                    u64 v = desc_load(a.tile_desc + my_tile);
-                    if ((v >> kStatusShift) == kStatusPrefix) e = v & kValueMask;
-                }
-                const u64 unknown = __ballot(e == kUnknown);
-                n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
-                if (all ? (n_ready == q_len) : (n_ready >= 1)) break;
-                if (!keep_waiting(a.abort_flag, spins, lane)) {
-                    ok = false;         // give up: drop everything that is parked
-                    n_ready = q_len;
-                    break;
-                }
-            }
-#else
-            e = 0;
-#endif
-            if (lane < n_ready) s_q_excl[slot] = e;
-            if (lane == 0) {
-                s_ok = ok ? 1 : 0;
-                s_ready = n_ready;
-#if !(ROSE_DIAG & 1)
-                STAT_ADD(a, 2, 1); STAT_ADD(a, 3, spins); STAT_ADD(a, 4, n_ready); STAT_ADD(a, 5, q_len);
-#endif
-            }
-        }
-        __syncthreads();
-        const int n_ready = s_ready;
+    // copy the n oldest parked tiles to the buckets (prefixes in excl[0..n)); returns ring entries freed
+    auto copy_out = [&](int n, const u64 *excl_by_age, bool ok) -> uint32_t {
         uint32_t freed = 0;
-        for (int i = 0; i < n_ready; ++i) {
+        for (int i = 0; i < n; ++i) {
             const int slot = (q_head + i) & (kQueue - 1);
             const uint32_t cnt = s_q_count[slot];
             freed += cnt;
-            if (s_ok && !(ROSE_DIAG & 2)) {
-                const u64 excl = s_q_excl[slot];
+            if (ok && !(ROSE_DIAG & 2)) {
+                const u64 excl = excl_by_age[i];
                 const uint32_t off = s_q_off[slot];
                 const BucketDev b = a.bucket[s_q_shard[slot]];
                 if (threadIdx.x == 0) {
@@ -533,14 +510,69 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
                 }
             }
         }
+        return freed;
+    };
+    auto pop = [&](int n) {      // forget the n oldest tiles (wave 0 shifts its lanes down)
+        q_head = (q_head + n) & (kQueue - 1);
+        q_len -= n;
+        if (wave == 0) {
+            wq_tile = __shfl(wq_tile, lane + n, 64);
+            wq_e = __shfl(wq_e, lane + n, 64);
+        }
+    };
+
+    // Blocking drain, for when there is no room to park (or at the end): waits until the oldest
+    // parked tile (all = false) or every parked tile (all = true) has its prefix.
+    auto drain = [&](bool all) {
+#if ROSE_STATS
+        const unsigned long long st_t0 = wall_clock64();
+        ++st_drains;
+#endif
+        __syncthreads();                               // parked entries visible; earlier copies done
+        ring_used -= ring_held;
+        ring_held = 0;
+        q_held = 0;
+        if (wave == 0) {
+            bool ok = true;
+            int n_ready = q_len;
+#if !(ROSE_DIAG & 1)
+            unsigned int spins = 0;
+            for (;;) {
+                if (lane < q_len && wq_e == kUnknown) {
+                    u64 v = desc_load(a.tile_desc + wq_tile);
+                    if ((v >> kStatusShift) == kStatusPrefix) wq_e = v & kValueMask;
+                }
+                const u64 unknown = __ballot(lane < q_len && wq_e == kUnknown);
+                n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
+                if (all ? (n_ready == q_len) : (n_ready >= 1 || q_len == 0)) break;   // q_len 0: only held space was needed
+                if (!keep_waiting(a.abort_flag, spins, lane)) {
+                    ok = false;         // give up: drop everything that is parked
+                    n_ready = q_len;
+                    break;
+                }
+            }
+#else
+            wq_e = 0;
+#endif
+            if (lane < n_ready) s_excl_sync[lane] = wq_e;
+            if (lane == 0) {
+                s_ok = ok ? 1 : 0;
+                s_ready = n_ready;
+            }
+        }
+        __syncthreads();
+        const int n_ready = __builtin_amdgcn_readfirstlane(s_ready);
+        const uint32_t freed = copy_out(n_ready, s_excl_sync, s_ok != 0);
         __syncthreads();                               // ring and queue slots may be reused
-        q_head = (q_head + n_ready) & (kQueue - 1);
-        q_len -= n_ready;
+        pop(n_ready);
         ring_used -= freed;
+#if ROSE_STATS
+        st_drain_clk += wall_clock64() - st_t0;
+#endif
     };
 
     // Tiles come from tickets (dynamic, so that faster workgroups take more): a ticket is fetched
-    // one batch ahead by thread 0 and handed to the others through LDS at the next barrier.
+    // one tile ahead by thread 0 and handed to the others through LDS at the next barrier.
     auto fetch_ticket = [&](uint32_t c) -> unsigned int {
         return __hip_atomic_fetch_add(a.ticket + c * (kTicketStride / sizeof(unsigned int)), 1u, __ATOMIC_RELAXED,
                                       __HIP_MEMORY_SCOPE_AGENT);
@@ -645,18 +677,39 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             }
         }
 
-        // exclusive rank of each of this lane's vectors inside the wave's span
+        // exclusive rank of each of this lane's vectors inside the wave's span: the per-vector
+        // counts (<= 8, wave totals <= 512) are scanned two at a time in 16-bit fields
         uint32_t rank[kIters];
         uint32_t wave_total = 0;
 #pragma unroll
-        for (int j = 0; j < kIters; ++j) {
-            uint32_t c = __popc(mask[j]);
-            uint32_t inc = wave_incl_scan(c);
-            rank[j] = wave_total + inc - c;
-            wave_total += __shfl(inc, 63, 64);
+        for (int j = 0; j < kIters; j += 2) {
+            const uint32_t c0 = __popc(mask[j]);
+            const uint32_t c1 = (j + 1 < kIters) ? __popc(mask[j + 1]) : 0u;
+            const uint32_t inc = wave_incl_scan(c0 | (c1 << 16));
+            const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+            rank[j] = wave_total + (inc & 0xFFFFu) - c0;
+            wave_total += tot & 0xFFFFu;
+            if (j + 1 < kIters) {
+                rank[j + 1] = wave_total + (inc >> 16) - c1;
+                wave_total += tot >> 16;
+            }
         }
         if (lane == 0) s_wave_total[parity][wave] = wave_total;
         if (request && threadIdx.x == 0) s_ticket[parity] = (int32_t)pending_ticket;
+        // wave 0 takes in the answers of the poll it sent at the end of the previous iteration
+        // (they arrived long ago) and tells everyone how many of the oldest tiles are ready
+        if (wave == 0) {
+#if !(ROSE_DIAG & 1)
+            if (poll_out && lane < q_len && wq_e == kUnknown && (polled >> kStatusShift) == kStatusPrefix)
+                wq_e = polled & kValueMask;
+#else
+            wq_e = 0;
+#endif
+            const u64 unknown = __ballot(lane < q_len && wq_e == kUnknown);
+            const int n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
+            if (lane < n_ready) s_excl[parity][lane] = wq_e;
+            if (lane == 0) s_nready[parity] = n_ready;
+        }
         __syncthreads();
         if (request) walk_accept(a, walk, request_lane, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket[parity]));
         uint32_t wave_excl = 0, tile_total = 0;
@@ -666,17 +719,34 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             if (w < wave) wave_excl += c;
             tile_total += c;
         }
-        parity ^= 1;
 
         // publish the count: a serving wave turns it into this tile's prefix
         if (threadIdx.x == 0 && !(ROSE_DIAG & 4))
             desc_store(a.tile_desc + tile, (kStatusAggregate << kStatusShift) | tile_total);
 
+        // what the previous iteration copied out is free now (everyone has passed the barrier)
+        ring_used -= ring_held;
+        ring_held = 0;
+        q_held = 0;
+        {   // copy out the parked tiles whose prefixes have arrived; their space is held one round
+            const int n_ready = __builtin_amdgcn_readfirstlane(s_nready[parity]);
+#if ROSE_STATS
+            ++st_iters;
+            st_async += n_ready;
+#endif
+            if (n_ready > 0) {
+                ring_held = copy_out(n_ready, s_excl[parity], true);
+                q_held = n_ready;
+                pop(n_ready);
+            }
+        }
+        parity ^= 1;
+
         const bool big = tile_total > (uint32_t)kRing;
         if (big) {
             if (q_len > 0) drain(true);
         } else {
-            while (q_len == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
+            while (q_len + q_held == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
         }
 
         const int32_t chain_last = a.chain_first[pc.shard + 1] - 1;
@@ -699,12 +769,15 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             }
             if (threadIdx.x == 0) {
                 const int slot = (q_head + q_len) & (kQueue - 1);
-                s_q_tile[slot] = tile;
                 s_q_count[slot] = tile_total;
                 s_q_off[slot] = ring_head;
                 s_q_shard[slot] = pc.shard;
                 s_q_seg[slot] = seg;
                 s_q_last[slot] = tile == chain_last;
+            }
+            if (wave == 0 && lane == q_len) {
+                wq_tile = tile;
+                wq_e = kUnknown;
             }
             ++q_len;
             ring_used += tile_total;
@@ -761,6 +834,11 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
             __syncthreads();                           // s_direct_excl / s_ok are reused
         }
 
+        // send the next poll: one lane per parked tile that has no prefix yet.  The answers are
+        // taken in at the next iteration, after that tile's own data has arrived, so nobody waits.
+        poll_out = q_len > 0;
+        if (wave == 0 && lane < q_len && wq_e == kUnknown) polled = desc_load(a.tile_desc + wq_tile);
+
         // the rare case that the next tile could not be named before the barrier above: name it
         // now and issue its loads late
         while (next_state == kWalkNeedTicket) {
@@ -779,7 +857,27 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(EncodeArgs a) {
         cur = nxt;
         tile = next;
     }
-    if (q_len > 0) drain(true);
+    while (q_len > 0) drain(true);
+#if ROSE_STATS
+    if (threadIdx.x == 0) {
+        unsigned long long *st = a.block_desc + a.n_blocks + (size_t)blockIdx.x * 8;
+        st[0] = st_iters; st[1] = st_drains; st[2] = st_async; st[3] = st_drain_clk; st[4] = wall_clock64() - st_clk0;
+    }
+#endif
+}
+
+// The two instantiations get their own register budgets: 4 waves per SIMD (128 VGPRs) fit the
+// bf16 kernel without spills, the fp32-master kernel holds twice the raw data and gets 3.
+template <int NEW_F32> __global__ void encode_kernel(EncodeArgs a);
+template <>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROSE_WAVES_PER_EU, ROSE_WAVES_PER_EU)))
+void encode_kernel<0>(EncodeArgs a) {
+    encode_body<0>(a);
+}
+template <>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void encode_kernel<1>(EncodeArgs a) {
+    encode_body<1>(a);
 }
 
 // ---------------------------------------------------------------------------------------------
