@@ -406,23 +406,25 @@ struct Walk {
     uint32_t lanes_done;        // counters that have run out
 };
 enum : int { kWalkTile = 0, kWalkNeedTicket = 1, kWalkDone = 2 };
-constexpr uint32_t kAllLanes = kTicketLanes == 32 ? 0xFFFFFFFFu : ((1u << kTicketLanes) - 1u);
 
 // counter the next request goes to (only called while some counter is left)
-__device__ __forceinline__ uint32_t walk_pick_lane(Walk &w) {
-    while (w.lanes_done & (1u << w.rr)) w.rr = (w.rr + 1) % kTicketLanes;
+__device__ __forceinline__ uint32_t walk_pick_lane(const EncodeArgs &a, Walk &w) {
+    while (w.lanes_done & (1u << w.rr)) w.rr = (w.rr + 1 == (uint32_t)a.n_lanes) ? 0 : w.rr + 1;
     const uint32_t c = w.rr;
-    w.rr = (w.rr + 1) % kTicketLanes;
+    w.rr = (w.rr + 1 == (uint32_t)a.n_lanes) ? 0 : w.rr + 1;
     return c;
+}
+__device__ __forceinline__ bool walk_lanes_left(const EncodeArgs &a, const Walk &w) {
+    return w.lanes_done != ((1u << a.n_lanes) - 1u);      // n_lanes <= kTicketLanes < 32
 }
 
 // take in the answer n of counter c: local ticket n of counter c is ticket n mod kBlock of group
-// (n / kBlock) * kTicketLanes + c
+// (n / kBlock) * n_lanes + c
 __device__ __forceinline__ void walk_accept(const EncodeArgs &a, Walk &w, uint32_t c, uint32_t n) {
     if (n >= (uint32_t)a.lane_tickets) {
         w.lanes_done |= 1u << c;
     } else {
-        w.next_ticket = (int32_t)(((n / kBlock) * kTicketLanes + c) * kBlock + (n & (kBlock - 1)));
+        w.next_ticket = (int32_t)(((n / kBlock) * (uint32_t)a.n_lanes + c) * kBlock + (n & (kBlock - 1)));
         w.have_next = true;
     }
 }
@@ -440,7 +442,7 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
             }
         }
         w.j = kBatch;
-        if (!w.have_next) return w.lanes_done == kAllLanes ? kWalkDone : kWalkNeedTicket;
+        if (!w.have_next) return walk_lanes_left(a, w) ? kWalkNeedTicket : kWalkDone;
         w.ticket = w.next_ticket;
         w.have_next = false;
         w.j = -1;
@@ -582,10 +584,10 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     walk.j = kBatch;
     walk.have_next = false;
     walk.next_ticket = 0;
-    walk.rr = blockIdx.x % kTicketLanes;
+    walk.rr = blockIdx.x % (uint32_t)a.n_lanes;
     walk.lanes_done = 0;
     auto fetch_ticket_now = [&]() {        // all threads; two barriers; needs a counter that is left
-        const uint32_t c = walk_pick_lane(walk);
+        const uint32_t c = walk_pick_lane(a, walk);
         if (threadIdx.x == 0) s_ticket_sync = (int32_t)fetch_ticket(c);
         __syncthreads();
         walk_accept(a, walk, c, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket_sync));
@@ -609,11 +611,11 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
     for (;;) {
         // ask for the next ticket as soon as the one fetched ahead has been taken into use
-        const bool request = !walk.have_next && walk.lanes_done != kAllLanes;
+        const bool request = !walk.have_next && walk_lanes_left(a, walk);
         uint32_t request_lane = 0;
         unsigned int pending_ticket = 0;
         if (request) {
-            request_lane = walk_pick_lane(walk);
+            request_lane = walk_pick_lane(a, walk);
             if (threadIdx.x == 0) pending_ticket = fetch_ticket(request_lane);
         }
 
@@ -842,7 +844,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         // the rare case that the next tile could not be named before the barrier above: name it
         // now and issue its loads late
         while (next_state == kWalkNeedTicket) {
-            if (!walk.have_next && walk.lanes_done != kAllLanes) fetch_ticket_now();
+            if (!walk.have_next && walk_lanes_left(a, walk)) fetch_ticket_now();
             next_state = walk_step(a, walk, &next);
             if (next_state == kWalkTile) {
                 nxt = tile_ctx(a, next);
@@ -1074,17 +1076,26 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
     if (server_wgs < 1) server_wgs = 1;
     int workers = resident - server_wgs;
     if (workers > a.n_tiles) workers = a.n_tiles;
-    // A worker that waits with a full queue relies on other workers to take the tickets that
-    // complete its blocks.  At most kTicketLanes groups of tickets are partly handed out at any
-    // time, so as long as the workers can park more tiles in total than those groups hold, some
-    // parked tile always belongs to a block whose tiles have all been taken.
-    if (workers < 1 ||
-        (workers < a.n_tiles && (int64_t)workers * kQueue <= (int64_t)kTicketLanes * kBlock * kBatch))
-        return (int)hipErrorInvalidValue;
+    // Progress with dynamic tickets.  A ticket stands for the tiles at one position of kBatch
+    // consecutive blocks, and the kBlock tickets of such a group of blocks come from one counter in
+    // order.  A worker waits only for prefixes of tiles it has published.  A block's prefixes need
+    // that block and all earlier blocks of its chain to be published: by induction over (group,
+    // slot in the batch) every holder of a ticket of a fully handed-out group gets through its
+    // batch; only holders of the one partly handed-out group can be stuck, until the remaining
+    // tickets of that group are taken, which needs a worker that holds none of them.  Hence: more
+    // workers than tickets in a group.  (Several counters would hand out several groups at once
+    // with no order between them; a worker that can hold a single tile, because the tile is too
+    // large to park, could then wait for a group that only it and its peers could complete.  That
+    // is why one counter is used unless the build asks for more and kQueue tiles always fit.)
+    if (workers < 1) return (int)hipErrorInvalidValue;
+    if (workers < a.n_tiles && workers <= kBlock) return (int)hipErrorInvalidValue;   // device holds too few workgroups
+    int lanes = kTicketLanes;
+    if (lanes > 1 && workers / (2 * kBlock) < lanes) lanes = workers / (2 * kBlock) < 1 ? 1 : workers / (2 * kBlock);
+    a.n_lanes = lanes;
     a.n_server_wgs = server_wgs;
     a.n_servers = server_wgs * kWaves;
     const int32_t n_groups = (a.n_blocks + kBatch - 1) / kBatch;         // groups of kBlock tickets
-    a.lane_tickets = ((n_groups + kTicketLanes - 1) / kTicketLanes) * kBlock;
+    a.lane_tickets = ((n_groups + lanes - 1) / lanes) * kBlock;
     // header, tile words and block words are one array
     const int64_t n_words = (int64_t)(kWsHeaderBytes / sizeof(u64)) + a.n_tiles + a.n_blocks;
     int reset_blocks = (int)((n_words + 1023) / 1024);

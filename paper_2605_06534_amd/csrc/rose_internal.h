@@ -77,7 +77,7 @@ struct EncodeArgs {
     int32_t n_server_wgs;                   // workgroups 0 .. n_server_wgs-1 serve prefixes, the rest walk tiles
     int32_t n_servers;                      // waves that serve prefixes (kWaves per serving workgroup)
     int32_t lane_tickets;                   // tickets each ticket counter hands out
-    int32_t pad;
+    int32_t n_lanes;                        // ticket counters in use (<= kTicketLanes)
     unsigned int *ticket;                   // workspace header: kTicketLanes counters, kTicketStride bytes apart
 };
 
@@ -90,15 +90,15 @@ constexpr int kBlock = 64;
 // Tickets come from kTicketLanes counters, each serving every kTicketLanes-th group of kBlock
 // tickets, so that the atomics spread over several memory channels.
 #ifndef ROSE_BATCH
-#define ROSE_BATCH 1
+#define ROSE_BATCH 4
 #endif
 #ifndef ROSE_TICKET_LANES
-#define ROSE_TICKET_LANES 16
+#define ROSE_TICKET_LANES 1
 #endif
 constexpr int kBatch = ROSE_BATCH;
 constexpr int kTicketLanes = ROSE_TICKET_LANES;
 constexpr size_t kTicketStride = 4096;
-static_assert(kTicketLanes >= 1 && kTicketLanes <= 32, "ticket lanes are tracked in a 32-bit mask");
+static_assert(kTicketLanes >= 1 && kTicketLanes < 32, "ticket lanes are tracked in a 32-bit mask");
 
 constexpr size_t kWsAbortOff = 0;
 constexpr size_t kWsTicketOff = kTicketStride;

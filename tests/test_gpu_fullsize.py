@@ -1,0 +1,160 @@
+"""Full-size GPU checks, in the launch configuration bench.py times: the library runs on the
+whole synthetic parameter set; the oracle is compared entry by entry on sampled tensors (it
+computes any single tensor in well under a second), and properties that hold at any size are
+checked on everything with plain torch ops: counts equal the popcount of the change mask,
+indices ascend inside a segment, and applying every bucket turns the receiver's copy of the old
+weights into the plainly sliced new weights, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_06534_amd as R
+from oracle import oracle
+from workloads import models, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def torch_shard(x, t, tp, d):
+    """Shard d of the full 2-D tensor x by plain slicing (test-side statement of the layout)."""
+    x = x.view(t["rows"], t["cols"])
+    rule = t["rule"]
+    if rule == R.REPLICATED:
+        return x.reshape(-1)
+    if rule == R.SPLIT_ROWS:
+        n = t["rows"] // tp
+        return x[d * n:(d + 1) * n].reshape(-1)
+    if rule == R.SPLIT_COLS:
+        n = t["cols"] // tp
+        return x[:, d * n:(d + 1) * n].reshape(-1)
+    parts, row0 = [], 0
+    for s in t["sections"]:
+        n = s // tp
+        parts.append(x[row0 + d * n:row0 + (d + 1) * n])
+        row0 += s
+    return torch.cat(parts, 0).reshape(-1)
+
+
+def host_bits(t):
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.float32:
+        return t.view(torch.int32).numpy().view(np.uint32)
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def new_as_bf16(n):
+    return n.to(torch.bfloat16) if n.dtype == torch.float32 else n
+
+
+def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None, **kw):
+    dev = "cuda"
+    olds, news = [], []
+    for _, _, o, n in synth.model_pairs(tensors, recipe, seed, dev, **kw):
+        olds.append(o)
+        news.append(n)
+    new_dtype = R.FP32_RNE if news[0].dtype == torch.float32 else R.BF16
+    plan = R.shard_plan(tensors, tp)
+    old_tab, new_tab = R.ptr_table(olds), R.ptr_table(news)
+    ws = R.workspace(plan)
+    if cap_frac is None:
+        cap_frac = min(1.0, 1.3 * density + 0.002)
+    buckets = [R.Bucket(int(plan.bucket_capacity(d) * cap_frac) + 4096, len(tensors)) for d in range(tp)]
+    print("  encode", flush=True)
+    R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
+    torch.cuda.synchronize()
+    totals = [R.bucket_check(plan, b) for b in buckets]
+    seg = [b.seg_off.cpu().numpy() for b in buckets]
+
+    # property: counts = popcount of the mask (times tp for replicated tensors)
+    print("  counts", flush=True)
+    grand = 0
+    for i, (t, o, n) in enumerate(zip(tensors, olds, news)):
+        changed = int((o.view(torch.int16) != new_as_bf16(n).view(torch.int16)).sum())
+        got = sum(int(seg[d][i + 1] - seg[d][i]) for d in range(tp))
+        assert got == changed * (tp if t["rule"] == R.REPLICATED else 1), (i, t["name"])
+        grand += got
+    assert grand == sum(totals)
+    for d in range(tp):
+        assert seg[d][0] == 0 and seg[d][-1] == totals[d] and (np.diff(seg[d]) >= 0).all()
+
+    # property: indices ascend strictly inside every segment (checked on the whole bucket at once:
+    # a drop in the index stream may only happen at a segment boundary)
+    print("  order", flush=True)
+    for d in range(tp):
+        idx = buckets[d].idx[:totals[d]]
+        if totals[d] > 1:
+            drops = torch.nonzero(idx[1:] <= idx[:-1]).flatten() + 1
+            starts = set(int(x) for x in seg[d])
+            assert all(int(x) in starts for x in drops.cpu()), "shard %d" % d
+
+    # oracle parity on the sampled tensors, every shard
+    print("  oracle on %d sampled tensors" % len(sample), flush=True)
+    for i in sample:
+        t = tensors[i]
+        want = oracle.encode_tensor(host_bits(olds[i]), host_bits(news[i]), t["rows"], t["cols"], t["rule"],
+                                    t["sections"], tp)
+        for d in range(tp):
+            a, b = int(seg[d][i]), int(seg[d][i + 1])
+            assert b - a == want[d][0].size, (i, d)
+            assert np.array_equal(buckets[d].idx[a:b].cpu().numpy(), want[d][0]), (i, d)
+            assert np.array_equal(buckets[d].val[a:b].cpu().numpy().view(np.uint16), want[d][1]), (i, d)
+
+    # property: apply(encode(old, new), slice(old)) == slice(new), all tensors, all shards
+    print("  apply + round trip", flush=True)
+    for d in range(tp):
+        dst = [torch_shard(o, t, tp, d).clone() for t, o in zip(tensors, olds)]
+        R.delta_apply(plan, d, buckets[d], R.ptr_table(dst))
+        torch.cuda.synchronize()
+        for i, (t, n) in enumerate(zip(tensors, news)):
+            want = torch_shard(new_as_bf16(n), t, tp, d)
+            assert torch.equal(dst[i].view(torch.int16), want.view(torch.int16)), (d, i, t["name"])
+        if d == tp - 1:   # dense path against the same slicing, last shard
+            R.dense_copy(plan, d, new_tab, new_dtype, R.ptr_table(dst))
+            torch.cuda.synchronize()
+            for i, (t, n) in enumerate(zip(tensors, news)):
+                assert torch.equal(dst[i].view(torch.int16), torch_shard(new_as_bf16(n), t, tp, d).view(torch.int16))
+        del dst
+    del olds, news, buckets
+    torch.cuda.empty_cache()
+    return totals
+
+
+def test_decoder7b_tp4_p05():
+    """7B-style decoder, TP=4, Bernoulli(0.05): the workload bench.py times."""
+    print("case: decoder7b tp=4 p=0.05 seed=0", flush=True)
+    ts = models.decoder_7b()
+    # embed, a norm, fused qkv, o (column blocks), gate_up, down of the first layer; the last
+    # layer's down, the final norm and lm_head
+    sample = [0, 1, 2, 3, 5, 6, len(ts) - 3, len(ts) - 2, len(ts) - 1]
+    totals = run_and_check(ts, 4, "bernoulli", 0, sample, density=0.05, p=0.05)
+    n = models.numel(ts)
+    assert abs(sum(totals) - 0.05 * n) < 6 * (n * 0.05 * 0.95) ** 0.5 + 0.05 * 4 * 65 * 4096
+
+
+@pytest.mark.parametrize("p", [0.001, 0.01, 0.1, 0.5])
+def test_flat_2pow30_density_sweep(p):
+    """One flat 2^30-element tensor, TP=1, int32 indices up to 2^30 - 1."""
+    print("case: flat 2^30 p=%g seed=0" % p, flush=True)
+    totals = run_and_check(models.flat(1 << 30), 1, "bernoulli", 0, sample=[0] if p <= 0.01 else [], density=p, p=p)
+    n = 1 << 30
+    assert abs(totals[0] - p * n) < 6 * (n * p * (1 - p)) ** 0.5
+
+
+def test_decoder32b_tp8_p02():
+    """32B-style GQA decoder, TP=8 (one KV head per shard), Bernoulli(0.02); old + new are 131 GB resident."""
+    print("case: decoder32b tp=8 p=0.02 seed=0", flush=True)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 165e9:
+        pytest.skip("needs about 160 GB of free device memory")
+    ts = models.decoder_32b()
+    sample = [1, 2, 3, 5, 6, len(ts) - 2]          # norm, GQA qkv, o, gate_up, down, final norm
+    run_and_check(ts, 8, "bernoulli", 0, sample, density=0.02, p=0.02)
+
+
+def test_decoder32b_tp8_fp32_master_clustered():
+    """fp32-master input with per-row Beta(0.5, 20) change rates, 32B shapes at 8 of 64 layers (the
+    full set with an fp32 copy does not leave room for the receiver's shards on one GPU)."""
+    print("case: decoder32b(8 layers) tp=8 clustered fp32 seed=0", flush=True)
+    ts = models.decoder_32b(layers=8)
+    sample = [0, 2, 3, 6, len(ts) - 1]
+    run_and_check(ts, 8, "clustered_f32", 0, sample, cap_frac=0.08, vocab_active=20000)
