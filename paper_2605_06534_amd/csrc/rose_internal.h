@@ -90,7 +90,7 @@ constexpr int kBlock = 64;
 // Tickets come from kTicketLanes counters, each serving every kTicketLanes-th group of kBlock
 // tickets, so that the atomics spread over several memory channels.
 #ifndef ROSE_BATCH
-#define ROSE_BATCH 4
+#define ROSE_BATCH 3
 #endif
 #ifndef ROSE_TICKET_LANES
 #define ROSE_TICKET_LANES 1
