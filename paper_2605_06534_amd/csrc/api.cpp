@@ -11,33 +11,43 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 
 // Copy the piece and tile tables to the current device once; later calls on the same device
 // reuse them.  A plan is bound to the first device it is used on.
-rose_status device_tables(const rose_plan *p, const rose::Piece **pieces, const int32_t **tile_piece) {
+rose_status device_tables(const rose_plan *p, const rose::Piece **pieces, const int32_t **tile_piece,
+                          const int32_t **local_numel = nullptr) {
     std::lock_guard<std::mutex> lock(p->mu);
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return ROSE_ERR_HIP;
     if (p->device == -1) {
         rose::Piece *dp = nullptr;
-        int32_t *dt = nullptr;
-        size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
-        if (hipMalloc(reinterpret_cast<void **>(&dp), pb) != hipSuccess) return ROSE_ERR_HIP;
-        if (hipMalloc(reinterpret_cast<void **>(&dt), tb) != hipSuccess) {
-            (void)hipFree(dp);
-            return ROSE_ERR_HIP;
+        int32_t *dt = nullptr, *dn = nullptr;
+        std::vector<int32_t> numel(p->n_tensors);
+        for (int32_t i = 0; i < p->n_tensors; ++i) {
+            const rose_tensor_desc &t = p->tensors[i];
+            numel[i] = (int32_t)(t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : p->tp));
         }
-        if (hipMemcpy(dp, p->pieces.data(), pb, hipMemcpyHostToDevice) != hipSuccess ||
-            hipMemcpy(dt, p->tile_piece.data(), tb, hipMemcpyHostToDevice) != hipSuccess) {
-            (void)hipFree(dp);
-            (void)hipFree(dt);
+        size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
+        size_t nb = numel.size() * sizeof(int32_t);
+        bool ok = hipMalloc(reinterpret_cast<void **>(&dp), pb) == hipSuccess &&
+                  hipMalloc(reinterpret_cast<void **>(&dt), tb) == hipSuccess &&
+                  hipMalloc(reinterpret_cast<void **>(&dn), nb) == hipSuccess &&
+                  hipMemcpy(dp, p->pieces.data(), pb, hipMemcpyHostToDevice) == hipSuccess &&
+                  hipMemcpy(dt, p->tile_piece.data(), tb, hipMemcpyHostToDevice) == hipSuccess &&
+                  hipMemcpy(dn, numel.data(), nb, hipMemcpyHostToDevice) == hipSuccess;
+        if (!ok) {
+            if (dp) (void)hipFree(dp);
+            if (dt) (void)hipFree(dt);
+            if (dn) (void)hipFree(dn);
             return ROSE_ERR_HIP;
         }
         p->d_pieces = dp;
         p->d_tile_piece = dt;
+        p->d_local_numel = dn;
         p->device = dev;
     } else if (p->device != dev) {
         return ROSE_ERR_ARG;
     }
     *pieces = p->d_pieces;
     *tile_piece = p->d_tile_piece;
+    if (local_numel) *local_numel = p->d_local_numel;
     return ROSE_OK;
 }
 
@@ -54,6 +64,7 @@ extern "C" void rose_shard_plan_destroy(rose_plan *p) {
     if (!p) return;
     if (p->d_pieces) (void)hipFree(p->d_pieces);
     if (p->d_tile_piece) (void)hipFree(p->d_tile_piece);
+    if (p->d_local_numel) (void)hipFree(p->d_local_numel);
     delete p;
 }
 
@@ -102,7 +113,11 @@ extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const ros
     if (s != ROSE_OK) return s;
     if (!aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
     rose::BucketDev b{bucket->idx, bucket->val, bucket->capacity, bucket->seg_off};
-    return rose::launch_apply(b, p->n_tensors, dst_ptrs, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+    const rose::Piece *pieces = nullptr;
+    const int32_t *tile_piece = nullptr, *local_numel = nullptr;
+    s = device_tables(p, &pieces, &tile_piece, &local_numel);
+    if (s != ROSE_OK) return s;
+    return rose::launch_apply(b, p->n_tensors, local_numel, dst_ptrs, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
 }
 
 extern "C" rose_status rose_dense_copy(const rose_plan *p, int32_t d, const void *const *new_ptrs,

@@ -6,6 +6,8 @@
 // kernel reads each weight once with 128-bit loads and writes only the changed entries.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "rose_internal.h"
 
 namespace rose {
@@ -195,11 +197,12 @@ __device__ __forceinline__ uint4 xor4(uint4 a, uint4 b) { return make_uint4(a.x 
 // A descriptor is one 64-bit word, status in the top two bits, value below, written and read with
 // relaxed device-scope atomics: the word carries all a reader needs, nothing else is ordered by it.
 //
-// Progress: worker w owns tiles w, w + n_workers, ... and the whole grid (workers and servers) is
-// resident at once: the launcher sizes it from the occupancy query.  A worker publishes a tile's
-// count before it ever waits for that tile's prefix, and waits only for tiles it has published;
-// a server waits for counts of its current block and for earlier blocks.  So every wait is for
-// something a running wave produces without waiting on the waiter.  Waits are bounded anyway:
+// Progress: the whole grid (workers and servers) is resident at once: the launcher sizes it from
+// the occupancy query.  A worker publishes a tile's count before it ever waits for that tile's
+// prefix, and the rules at struct Walk keep it from waiting for a block that still needs a count
+// from the waiter itself; a server waits for counts of its current block and for earlier blocks.
+// So every wait is for something a running wave produces without waiting on the waiter.  Waits
+// are bounded anyway:
 // after ROSE_SPIN_LIMIT failed polls, or once the abort flag is set, a wave stops waiting, sets
 // the flag, and the launch is reported as failed; every wave always reaches the end of the kernel.
 // ---------------------------------------------------------------------------------------------
@@ -347,13 +350,13 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 // so the order (wave, step, lane, element) is ascending local index.
 // ---------------------------------------------------------------------------------------------
 #ifndef ROSE_RING
-#define ROSE_RING 4096
+#define ROSE_RING 8192
 #endif
 #ifndef ROSE_WAVES_PER_EU
 #define ROSE_WAVES_PER_EU 4     // register budget of the encode kernel: 512 / 4 = 128 VGPRs
 #endif
 #ifndef ROSE_QUEUE
-#define ROSE_QUEUE 8
+#define ROSE_QUEUE 16
 #endif
 constexpr int kRing = ROSE_RING;        // entries parked per workgroup (power of two)
 constexpr int kQueue = ROSE_QUEUE;      // tiles parked per workgroup (<= 64)
@@ -398,39 +401,40 @@ __device__ __forceinline__ int32_t ticket_tile(const EncodeArgs &a, int32_t tick
 }
 
 // A worker's position in the tile order it is given by its tickets (uniform state).
+//
+// Waiting and tickets.  A worker may wait for the prefix of a parked tile X only while every tile
+// it holds a ticket for and has not published lies in a later block than X: then the earliest
+// block that is not fully published never depends on a waiting worker, and all waits end.  Tickets
+// are taken in order, so the tiles of a worker's tickets lie in later and later groups, except
+// when two tickets in a row fall into the SAME group (few workers are taking tickets, e.g. while
+// most of them wait).  Such a pair is handled with care: from the moment the second ticket is
+// accepted nothing waits until the counts of all tiles of both tickets are published by a
+// count-only pass; then those tiles are walked again ("redo", without publishing) in the normal
+// way.  While redoing, no further ticket is asked for.
 struct Walk {
-    int32_t ticket, j;          // current ticket and batch slot
+    int32_t ticket, j;          // ticket in use (-1: none yet) and its batch slot
     int32_t next_ticket;        // ticket fetched ahead of time
+    int32_t redo_through;       // last ticket of a redo
     bool have_next;
-    uint32_t rr;                // ticket counter to ask next (round robin)
-    uint32_t lanes_done;        // counters that have run out
+    bool exhausted;             // the counter has run out
+    bool careful;               // a same-group ticket was accepted; its counts are not published yet
+    bool redo;                  // tiles up to the end of ticket redo_through are published already
 };
 enum : int { kWalkTile = 0, kWalkNeedTicket = 1, kWalkDone = 2 };
 
-// counter the next request goes to (only called while some counter is left)
-__device__ __forceinline__ uint32_t walk_pick_lane(const EncodeArgs &a, Walk &w) {
-    while (w.lanes_done & (1u << w.rr)) w.rr = (w.rr + 1 == (uint32_t)a.n_lanes) ? 0 : w.rr + 1;
-    const uint32_t c = w.rr;
-    w.rr = (w.rr + 1 == (uint32_t)a.n_lanes) ? 0 : w.rr + 1;
-    return c;
-}
-__device__ __forceinline__ bool walk_lanes_left(const EncodeArgs &a, const Walk &w) {
-    return w.lanes_done != ((1u << a.n_lanes) - 1u);      // n_lanes <= kTicketLanes < 32
-}
-
-// take in the answer n of counter c: local ticket n of counter c is ticket n mod kBlock of group
-// (n / kBlock) * n_lanes + c
-__device__ __forceinline__ void walk_accept(const EncodeArgs &a, Walk &w, uint32_t c, uint32_t n) {
-    if (n >= (uint32_t)a.lane_tickets) {
-        w.lanes_done |= 1u << c;
+// take in the counter's answer n
+__device__ __forceinline__ void walk_accept(const EncodeArgs &a, Walk &w, uint32_t n) {
+    if (n >= (uint32_t)a.n_tickets) {
+        w.exhausted = true;
     } else {
-        w.next_ticket = (int32_t)(((n / kBlock) * (uint32_t)a.n_lanes + c) * kBlock + (n & (kBlock - 1)));
+        w.next_ticket = (int32_t)n;
         w.have_next = true;
+        if (w.ticket >= 0 && (int32_t)n / kBlock == w.ticket / kBlock) w.careful = true;
     }
 }
 
 // Advance to the next tile.  kWalkNeedTicket: the current ticket is used up and no further one
-// is at hand (ask a counter, then call again); kWalkDone: no tiles are left.
+// is at hand (ask the counter, then call again); kWalkDone: no tiles are left.
 __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *tile) {
     for (;;) {
         while (w.j + 1 < kBatch) {
@@ -442,7 +446,8 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
             }
         }
         w.j = kBatch;
-        if (!w.have_next) return walk_lanes_left(a, w) ? kWalkNeedTicket : kWalkDone;
+        if (w.redo && w.ticket == w.redo_through) w.redo = false;
+        if (!w.have_next) return w.exhausted ? kWalkDone : kWalkNeedTicket;
         w.ticket = w.next_ticket;
         w.have_next = false;
         w.j = -1;
@@ -451,19 +456,20 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
 
 template <int NEW_F32>
 __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
-    __shared__ uint32_t s_ring_idx[kRing];
-    __shared__ uint16_t s_ring_val[kRing];
+    __shared__ uint32_t s_ring[kRing];      // an entry: offset inside its tile << 16 | value
     __shared__ uint32_t s_wave_total[2][kWaves];
     __shared__ u64 s_excl[2][kQueue];       // prefixes of the tiles an iteration copies out, oldest first
     __shared__ u64 s_excl_sync[kQueue];     // the same for a blocking drain
     __shared__ int32_t s_nready[2];
     __shared__ uint32_t s_q_count[kQueue];
     __shared__ uint32_t s_q_off[kQueue];
+    __shared__ uint32_t s_q_base[kQueue];   // local index of the tile's first element
     __shared__ int32_t s_q_shard[kQueue];
     __shared__ int32_t s_q_seg[kQueue];     // tensor whose segment starts with this tile, else -1
     __shared__ int32_t s_q_last[kQueue];    // 1 if the tile is the last of its chain
     __shared__ int32_t s_ok, s_ready;
     __shared__ int32_t s_ticket[2], s_ticket_sync;
+    __shared__ uint32_t s_count_only[kWaves];
     __shared__ u64 s_direct_excl;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -497,7 +503,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             freed += cnt;
             if (ok && !(ROSE_DIAG & 2)) {
                 const u64 excl = excl_by_age[i];
-                const uint32_t off = s_q_off[slot];
+                const uint32_t off = s_q_off[slot], base = s_q_base[slot];
                 const BucketDev b = a.bucket[s_q_shard[slot]];
                 if (threadIdx.x == 0) {
                     if (s_q_seg[slot] >= 0) b.seg_off[s_q_seg[slot]] = (int64_t)excl;
@@ -506,8 +512,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 for (uint32_t k = threadIdx.x; k < cnt; k += kThreads) {
                     const u64 pos = excl + k;
                     if (pos < (u64)b.capacity) {
-                        b.idx[pos] = (int32_t)s_ring_idx[(off + k) & (kRing - 1)];
-                        b.val[pos] = s_ring_val[(off + k) & (kRing - 1)];
+                        const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
+                        b.idx[pos] = (int32_t)(base + (entry >> 16));
+                        b.val[pos] = (uint16_t)entry;
                     }
                 }
             }
@@ -575,23 +582,44 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
     // Tiles come from tickets (dynamic, so that faster workgroups take more): a ticket is fetched
     // one tile ahead by thread 0 and handed to the others through LDS at the next barrier.
-    auto fetch_ticket = [&](uint32_t c) -> unsigned int {
-        return __hip_atomic_fetch_add(a.ticket + c * (kTicketStride / sizeof(unsigned int)), 1u, __ATOMIC_RELAXED,
-                                      __HIP_MEMORY_SCOPE_AGENT);
+    auto fetch_ticket = [&]() -> unsigned int {
+        return __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     Walk walk;
-    walk.ticket = 0;
+    walk.ticket = -1;
     walk.j = kBatch;
-    walk.have_next = false;
     walk.next_ticket = 0;
-    walk.rr = blockIdx.x % (uint32_t)a.n_lanes;
-    walk.lanes_done = 0;
-    auto fetch_ticket_now = [&]() {        // all threads; two barriers; needs a counter that is left
-        const uint32_t c = walk_pick_lane(a, walk);
-        if (threadIdx.x == 0) s_ticket_sync = (int32_t)fetch_ticket(c);
+    walk.redo_through = 0;
+    walk.have_next = false;
+    walk.exhausted = false;
+    walk.careful = false;
+    walk.redo = false;
+    auto fetch_ticket_now = [&]() {        // all threads; two barriers; no waiting
+        if (threadIdx.x == 0) s_ticket_sync = (int32_t)fetch_ticket();
         __syncthreads();
-        walk_accept(a, walk, c, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket_sync));
+        walk_accept(a, walk, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket_sync));
         __syncthreads();
+    };
+    // Count-only pass over one tile (all threads, rolled loads: this is rare): publishes its count.
+    auto publish_count = [&](int32_t t) {
+        const TileCtx c = tile_ctx(a, t);
+        uint32_t cnt = 0;
+#pragma unroll 1
+        for (int j = 0; j < kIters; ++j) {
+            const uint32_t k = c.k_tile + (uint32_t)wave * kWaveSpan + (uint32_t)(j * 64 + lane) * kVec;
+            const uint4 o = load_vec_general<0>(c.old_base, c.pc, k);
+            const uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, k);
+            cnt += __popc(nz16_mask(xor4(o, n)));
+        }
+        const uint32_t wave_cnt = (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(cnt), 63);
+        __syncthreads();                               // earlier readers of s_count_only are done
+        if (lane == 0) s_count_only[wave] = wave_cnt;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t total = 0;
+            for (int w = 0; w < kWaves; ++w) total += s_count_only[w];
+            if (!(ROSE_DIAG & 4)) desc_store(a.tile_desc + t, (kStatusAggregate << kStatusShift) | total);
+        }
     };
     int32_t tile = -1;
     for (;;) {
@@ -600,6 +628,8 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         if (st == kWalkDone) return;
         fetch_ticket_now();
     }
+    walk.careful = false;                              // nothing is parked yet, nothing has waited
+    bool cur_redo = false;
     TileCtx cur = tile_ctx(a, tile);
     RawTile<0> raw_old;
     RawTile<NEW_F32> raw_new;
@@ -611,13 +641,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
     for (;;) {
         // ask for the next ticket as soon as the one fetched ahead has been taken into use
-        const bool request = !walk.have_next && walk_lanes_left(a, walk);
-        uint32_t request_lane = 0;
+        const bool request = !walk.have_next && !walk.exhausted && !walk.redo;
         unsigned int pending_ticket = 0;
-        if (request) {
-            request_lane = walk_pick_lane(a, walk);
-            if (threadIdx.x == 0) pending_ticket = fetch_ticket(request_lane);
-        }
+        if (request && threadIdx.x == 0) pending_ticket = fetch_ticket();
 
         const Piece pc = cur.pc;
         const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
@@ -669,6 +695,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         // the next tile's loads go out now and stay in flight during everything below
         int32_t next = -1;
         int next_state = walk_step(a, walk, &next);     // kWalkNeedTicket: decided after the barrier
+        bool nxt_redo = walk.redo;
         TileCtx nxt = cur;
         if (next_state == kWalkTile) {
             nxt = tile_ctx(a, next);
@@ -713,7 +740,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             if (lane == 0) s_nready[parity] = n_ready;
         }
         __syncthreads();
-        if (request) walk_accept(a, walk, request_lane, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket[parity]));
+        if (request) walk_accept(a, walk, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket[parity]));
         uint32_t wave_excl = 0, tile_total = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
@@ -723,7 +750,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         }
 
         // publish the count: a serving wave turns it into this tile's prefix
-        if (threadIdx.x == 0 && !(ROSE_DIAG & 4))
+        if (threadIdx.x == 0 && !cur_redo && !(ROSE_DIAG & 4))
             desc_store(a.tile_desc + tile, (kStatusAggregate << kStatusShift) | tile_total);
 
         // what the previous iteration copied out is free now (everyone has passed the barrier)
@@ -744,8 +771,12 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         }
         parity ^= 1;
 
+        // A same-group ticket has just been accepted: nothing may wait now.  This tile is not
+        // parked; it is walked again after the count-only pass at the end of the iteration.
+        const bool skip = walk.careful;
         const bool big = tile_total > (uint32_t)kRing;
-        if (big) {
+        if (skip) {
+        } else if (big) {
             if (q_len > 0) drain(true);
         } else {
             while (q_len + q_held == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
@@ -753,19 +784,19 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
         const int32_t chain_last = a.chain_first[pc.shard + 1] - 1;
         const int32_t seg = ((pc.flags & kPieceFirst) && tile == pc.first_tile) ? pc.tensor : -1;
-        if (!big) {
+        if (skip) {
+        } else if (!big) {
             // park the entries: ring slot = ring_head + rank inside the tile
             const uint32_t base = ring_head + wave_excl;
 #pragma unroll
             for (int j = 0; j < kIters; ++j) {
                 uint32_t m = mask[j];
                 uint32_t slot = base + rank[j];
-                const uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
+                const uint32_t in_tile0 = (uint32_t)wave * kWaveSpan + (uint32_t)(j * 64 + lane) * kVec;
                 while (m && !(ROSE_DIAG & 8)) {
                     const uint32_t e = __ffs(m) - 1;
                     m &= m - 1;
-                    s_ring_idx[slot & (kRing - 1)] = local0 + e;
-                    s_ring_val[slot & (kRing - 1)] = (uint16_t)pick16(nv[j], e);
+                    s_ring[slot & (kRing - 1)] = ((in_tile0 + e) << 16) | (pick16(nv[j], e) & 0xFFFFu);
                     ++slot;
                 }
             }
@@ -773,6 +804,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 const int slot = (q_head + q_len) & (kQueue - 1);
                 s_q_count[slot] = tile_total;
                 s_q_off[slot] = ring_head;
+                s_q_base[slot] = (uint32_t)pc.local_base + cur.k_tile;
                 s_q_shard[slot] = pc.shard;
                 s_q_seg[slot] = seg;
                 s_q_last[slot] = tile == chain_last;
@@ -843,9 +875,46 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
         // the rare case that the next tile could not be named before the barrier above: name it
         // now and issue its loads late
-        while (next_state == kWalkNeedTicket) {
-            if (!walk.have_next && walk_lanes_left(a, walk)) fetch_ticket_now();
+        bool late = false;
+        bool redo_cur = skip;                          // this iteration's tile was not parked
+        for (;;) {
+            if (walk.careful) {
+                // the ticket in use (tA) and the one just accepted (tB) are of one group: publish
+                // the counts of everything not yet published, then walk those tiles again
+                const int32_t tA = walk.ticket, tB = walk.next_ticket;
+                int32_t j_from = kBatch;               // first slot of tA to walk again
+                if (redo_cur)
+                    for (int32_t j = 0; j < kBatch; ++j)
+                        if (ticket_tile(a, tA, j) == tile) j_from = j;
+                redo_cur = false;
+                for (int32_t j = j_from + 1; j < kBatch; ++j) {
+                    const int32_t t = ticket_tile(a, tA, j);
+                    if (t >= 0) publish_count(t);
+                }
+                for (int32_t j = 0; j < kBatch; ++j) {
+                    const int32_t t = ticket_tile(a, tB, j);
+                    if (t >= 0) publish_count(t);
+                }
+                __syncthreads();
+                if (threadIdx.x == 0)                  // diagnostic word: how often this happened
+                    __hip_atomic_fetch_add(a.abort_flag + kWsCarefulWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                walk.careful = false;
+                walk.redo = true;
+                walk.redo_through = tB;
+                walk.j = j_from - 1;
+                next_state = walk_step(a, walk, &next);
+                late = true;
+            }
+            if (next_state != kWalkNeedTicket) break;
+            if (!walk.have_next && !walk.exhausted) {
+                fetch_ticket_now();
+                if (walk.careful) continue;
+            }
             next_state = walk_step(a, walk, &next);
+            late = true;
+        }
+        if (late) {
+            nxt_redo = walk.redo;
             if (next_state == kWalkTile) {
                 nxt = tile_ctx(a, next);
                 if (nxt.vec) {
@@ -857,6 +926,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         }
         if (next_state == kWalkDone) break;
         cur = nxt;
+        cur_redo = nxt_redo;
         tile = next;
     }
     while (q_len > 0) drain(true);
@@ -883,78 +953,187 @@ void encode_kernel<1>(EncodeArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// apply: persistent grid over chunks of a bucket's entries; entries are in ascending local index
-// inside a segment, so neighbouring lanes store into the same or neighbouring lines.
+// apply (App. F S2D): every entry's value goes to its local index of the receiver's copy.
+//
+// Scattered 2-byte stores reach memory as byte-masked partial writes of the lines they touch,
+// which the memory side turns into slow read-modify-writes (measured: about 3 TB/s of line
+// traffic).  So the kernel does the read-modify-write itself, one 64-byte line at a time and with
+// 128-bit accesses: a wave takes 64 consecutive entries (ascending local index inside a segment,
+// so the entries of a line are neighbours), finds the distinct lines they touch, loads those lines
+// into LDS, patches the entries in, and stores the lines back whole.
+//
+// A line's entries may straddle two waves' chunks (a line holds at most 32 entries, a chunk 64):
+// the line belongs to the wave that holds its FIRST entry; that wave also applies the entries of
+// its last line that lie in the next chunk, and the next wave skips them.  Entries whose own
+// 16-byte part of the line is not entirely inside the tensor (the last few elements of a tensor
+// whose size is not a multiple of 8) and entries of tensors that are not 16-byte aligned are stored
+// directly; the line path never touches those bytes.
 // ---------------------------------------------------------------------------------------------
-#ifndef ROSE_APPLY_RFO
-#define ROSE_APPLY_RFO 0
-#endif
-constexpr int kApplyPerLane = 4;
 constexpr int kApplyThreads = 256;
-constexpr int kApplyChunk = kApplyThreads * kApplyPerLane;
+constexpr int kApplyWaves = kApplyThreads / 64;
+constexpr int kLineElems = 32;                  // 64-byte line of 16-bit elements
+constexpr int kLineShift = 5;
+// a wave rewrites whole lines when its entries average at least NUM / DEN per line
+#ifndef ROSE_APPLY_LINE_NUM
+#define ROSE_APPLY_LINE_NUM 3
+#define ROSE_APPLY_LINE_DEN 2
+#endif
 
-__global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors, void *const *dst_ptrs) {
+__device__ __forceinline__ void lds_wave_fence() {
+    // LDS operations of one wave are carried out in order; this keeps the compiler from moving
+    // them across and waits for the ones issued so far.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
+// Largest t in [0, n) with seg_off[t] <= e, for a wave-uniform e < seg_off[n]: a 64-ary search,
+// one parallel probe per round (two rounds up to 4096 tensors).
+__device__ __forceinline__ int32_t wave_find_segment(const int64_t *seg_off, int32_t n, int64_t e, int lane) {
+    int32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int32_t step = (hi - lo + 63) >> 6;
+        const int32_t probe = lo + lane * step;
+        const bool le = probe < hi && seg_off[probe] <= e;   // true on a prefix of the lanes, lane 0 included
+        const int k = __popcll(__ballot(le)) - 1;
+        lo += k * step;
+        hi = hi < lo + step ? hi : lo + step;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors,
+                                                              const int32_t *local_numel, void *const *dst_ptrs) {
+    __shared__ uint4 s_line[kApplyWaves][64][4];        // wave, line slot, 16-byte part
+    __shared__ u64 s_addr[kApplyWaves][64];             // address of the line
+    __shared__ int32_t s_parts[kApplyWaves][64];        // 16-byte parts of the line inside the tensor
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t total = b.seg_off[n_tensors];
     if (total > b.capacity) total = b.capacity;
-    for (int64_t e0 = (int64_t)blockIdx.x * kApplyChunk; e0 < total; e0 += (int64_t)gridDim.x * kApplyChunk) {
-        // tensor of the chunk's first entry: largest t with seg_off[t] <= e0 (uniform search)
-        int32_t lo = 0, hi = n_tensors;
-        while (hi - lo > 1) {
-            int32_t mid = (lo + hi) >> 1;
-            if (b.seg_off[mid] <= e0) lo = mid; else hi = mid;
-        }
-        int64_t e = e0 + (int64_t)threadIdx.x * kApplyPerLane;
-        if (e >= total) continue;
-        int32_t t = lo;
+
+    for (int64_t wbase = ((int64_t)blockIdx.x * kApplyWaves + wave) * 64; wbase < total;
+         wbase += (int64_t)gridDim.x * kApplyThreads) {
+        const int64_t e = wbase + lane, e2 = e + 64;
+        const bool valid = e < total;
+        // everything that depends on the entry numbers alone is requested first
+        const int32_t idx = valid ? b.idx[e] : 0;
+        const uint32_t val = valid ? b.val[e] : 0u;
+        const int32_t idx_before = (lane == 0 && wbase > 0) ? b.idx[wbase - 1] : 0;
+        const bool look = lane < kLineElems && e2 < total;
+        const int32_t idx2 = look ? b.idx[e2] : 0;
+        const uint32_t val2 = look ? b.val[e2] : 0u;
+
+        // tensor of the wave's first entry, then of each lane's entry
+        int32_t t = wave_find_segment(b.seg_off, n_tensors, wbase, lane);
+        const int64_t seg_start0 = b.seg_off[t];
         int64_t seg_end = b.seg_off[t + 1];
-        int32_t ix[kApplyPerLane];
-        uint32_t vv[kApplyPerLane];
-        if (e + kApplyPerLane <= total) {
-            int4 i4 = *reinterpret_cast<const int4 *>(b.idx + e);
-            uint2 v2 = *reinterpret_cast<const uint2 *>(b.val + e);
-            ix[0] = i4.x; ix[1] = i4.y; ix[2] = i4.z; ix[3] = i4.w;
-            vv[0] = v2.x & 0xFFFFu; vv[1] = v2.x >> 16; vv[2] = v2.y & 0xFFFFu; vv[3] = v2.y >> 16;
-        } else {
-#pragma unroll
-            for (int i = 0; i < kApplyPerLane; ++i) {
-                bool ok = e + i < total;
-                ix[i] = ok ? b.idx[e + i] : 0;
-                vv[i] = ok ? b.val[e + i] : 0u;
-            }
+        while (valid && e >= seg_end) {
+            ++t;
+            seg_end = b.seg_off[t + 1];
         }
-        uint16_t *dst = nullptr;
-        bool have = false;
-        uint16_t *target[kApplyPerLane];
-#pragma unroll
-        for (int i = 0; i < kApplyPerLane; ++i) {
-            target[i] = nullptr;
-            int64_t ei = e + i;
-            if (ei >= total) continue;
-            while (ei >= seg_end) {
-                ++t;
-                seg_end = b.seg_off[t + 1];
-                have = false;
-            }
-            if (!have) {
-                dst = static_cast<uint16_t *>(dst_ptrs[t]);
-                have = true;
-            }
-            target[i] = dst + ix[i];
+        uint16_t *dst = valid ? static_cast<uint16_t *>(dst_ptrs[t]) : nullptr;
+        const int32_t numel = valid ? local_numel[t] : 0;
+        // may this entry go through the line path?  (depends on the entry alone)
+        const bool ok = valid && (((uintptr_t)dst) & 15u) == 0 && (idx | 7) < numel;
+        const u64 key = valid ? (((u64)(uint32_t)t << 32) | (uint32_t)(idx >> kLineShift)) : ~0ull;
+
+        // same line as the entry before?  lane 0 looks at the last entry of the previous chunk
+        u64 prev_key = __shfl_up(key, 1, 64);
+        if (lane == 0)
+            prev_key = wbase > seg_start0 ? (((u64)(uint32_t)t << 32) | (uint32_t)(idx_before >> kLineShift)) : ~0ull - 1;
+        const bool same = valid && key == prev_key;
+        // leading lanes that continue the previous chunk's last line belong to the previous wave
+        const u64 not_same = __ballot(!same);
+        const int first_own = not_same ? __ffsll((long long)not_same) - 1 : 64;
+        const bool owned = ok && lane >= first_own;
+        const bool direct = valid && !ok;
+
+        // entries of the next chunk that still lie in this chunk's last line
+        const u64 key63 = __shfl(key, 63, 64);
+        const bool own63 = __shfl((int)owned, 63, 64) != 0;
+        const int64_t seg_end63 = __shfl(seg_end, 63, 64);
+        const int32_t numel63 = __shfl(numel, 63, 64);
+        const bool ext = own63 && look && e2 < seg_end63 &&
+                         ((key63 & ~0xffffffffull) | (uint32_t)(idx2 >> kLineShift)) == key63 && (idx2 | 7) < numel63;
+
+        // distinct lines of the owned entries
+        const bool prev_owned = __shfl_up((int)owned, 1, 64) != 0 && lane > 0;
+        const bool head = owned && (!prev_owned || !same);
+        const u64 heads = __ballot(head);
+        const int n_lines = __popcll(heads);
+        const int slot = __popcll(heads & ((2ull << lane) - 1)) - 1;      // line slot of an owned lane
+        // Few entries per line: rewriting whole lines moves more bytes than it saves, store directly.
+        const int n_owned = __popcll(__ballot(owned)) + __popcll(__ballot(ext));
+        if (n_lines * ROSE_APPLY_LINE_NUM > n_owned * ROSE_APPLY_LINE_DEN) {
+            if (owned || direct) dst[idx] = (uint16_t)val;
+            uint16_t *dst63 = reinterpret_cast<uint16_t *>((uintptr_t)__shfl((u64)(uintptr_t)dst, 63, 64));
+            if (ext) dst63[idx2] = (uint16_t)val2;
+            continue;
         }
-#if ROSE_APPLY_RFO
-        // Read each target first: the line is then complete in L2 and leaves it as a full-line
-        // write instead of a byte-masked partial one.
-        uint32_t seen = 0;
-#pragma unroll
-        for (int i = 0; i < kApplyPerLane; ++i)
-            if (target[i]) seen += *target[i];
-        asm volatile("" ::"v"(seen));
-#endif
-#pragma unroll
-        for (int i = 0; i < kApplyPerLane; ++i)
-            if (target[i]) *target[i] = (uint16_t)vv[i];
+        if (head) {
+            const int32_t line_first = (idx >> kLineShift) << kLineShift;
+            s_addr[wave][slot] = (u64)(uintptr_t)(dst + line_first);
+            int32_t parts = (numel - line_first) >> 3;
+            s_parts[wave][slot] = parts > 4 ? 4 : parts;
+        }
+        lds_wave_fence();
+
+        // load the lines: four lanes per line, sixteen lines per round
+        for (int r = 0; r * 16 < n_lines; ++r) {
+            const int sl = r * 16 + (lane >> 2), part = lane & 3;
+            if (sl < n_lines && part < s_parts[wave][sl])
+                s_line[wave][sl][part] = gload16(reinterpret_cast<const char *>((uintptr_t)s_addr[wave][sl]) + part * 16);
+        }
+        lds_wave_fence();
+
+        // patch
+        uint16_t *lines16 = reinterpret_cast<uint16_t *>(&s_line[wave][0][0]);
+        if (owned) lines16[slot * kLineElems + (idx & (kLineElems - 1))] = (uint16_t)val;
+        if (ext) lines16[(n_lines - 1) * kLineElems + (idx2 & (kLineElems - 1))] = (uint16_t)val2;
+        lds_wave_fence();
+
+        // store the lines back whole
+        for (int r = 0; r * 16 < n_lines; ++r) {
+            const int sl = r * 16 + (lane >> 2), part = lane & 3;
+            if (sl < n_lines && part < s_parts[wave][sl])
+                gstore16(reinterpret_cast<char *>((uintptr_t)s_addr[wave][sl]) + part * 16, s_line[wave][sl][part]);
+        }
+        if (direct) dst[idx] = (uint16_t)val;
+        lds_wave_fence();                               // the LDS slots are reused by the next round
     }
 }
+
+#ifdef ROSE_APPLY_SCATTER
+// plain scatter: a wave takes 256 consecutive entries, lane l the entries l, l + 64, ...
+__global__ __launch_bounds__(kApplyThreads) void apply_scatter_kernel(BucketDev b, int32_t n_tensors,
+                                                                      void *const *dst_ptrs) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t total = b.seg_off[n_tensors];
+    if (total > b.capacity) total = b.capacity;
+    for (int64_t wbase = ((int64_t)blockIdx.x * kApplyWaves + wave) * 256; wbase < total;
+         wbase += (int64_t)gridDim.x * kApplyThreads * 4) {
+        int32_t ix[4];
+        uint16_t vv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t e = wbase + i * 64 + lane;
+            ix[i] = e < total ? b.idx[e] : 0;
+            vv[i] = e < total ? b.val[e] : (uint16_t)0;
+        }
+        int32_t t = wave_find_segment(b.seg_off, n_tensors, wbase, lane);
+        int64_t seg_end = b.seg_off[t + 1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t e = wbase + i * 64 + lane;
+            if (e < total) {
+                while (e >= seg_end) {
+                    ++t;
+                    seg_end = b.seg_off[t + 1];
+                }
+                static_cast<uint16_t *>(dst_ptrs[t])[ix[i]] = vv[i];
+            }
+        }
+    }
+}
+#endif
 
 // ---------------------------------------------------------------------------------------------
 // dense copy of one shard: the same tiles as encode, moved instead of compared.
@@ -1076,26 +1255,21 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
     if (server_wgs < 1) server_wgs = 1;
     int workers = resident - server_wgs;
     if (workers > a.n_tiles) workers = a.n_tiles;
-    // Progress with dynamic tickets.  A ticket stands for the tiles at one position of kBatch
-    // consecutive blocks, and the kBlock tickets of such a group of blocks come from one counter in
-    // order.  A worker waits only for prefixes of tiles it has published.  A block's prefixes need
-    // that block and all earlier blocks of its chain to be published: by induction over (group,
-    // slot in the batch) every holder of a ticket of a fully handed-out group gets through its
-    // batch; only holders of the one partly handed-out group can be stuck, until the remaining
-    // tickets of that group are taken, which needs a worker that holds none of them.  Hence: more
-    // workers than tickets in a group.  (Several counters would hand out several groups at once
-    // with no order between them; a worker that can hold a single tile, because the tile is too
-    // large to park, could then wait for a group that only it and its peers could complete.  That
-    // is why one counter is used unless the build asks for more and kQueue tiles always fit.)
+    // tuning and test knob: fewer workers than the device holds (never fewer than the progress
+    // argument below needs)
+    if (const char *e = std::getenv("ROSE_ENCODE_WORKERS")) {
+        const int w = std::atoi(e);
+        if (w > kBlock && w < workers) workers = w;
+    }
+    // Progress with dynamic tickets: see the comment at struct Walk.  A worker that waits holds no
+    // unpublished tile in the block it waits for or in an earlier one; what it waits for can still
+    // need tickets of a partly handed-out group to be taken, by a worker that holds none of that
+    // group's kBlock tickets.  Hence: more workers than tickets in a group.
     if (workers < 1) return (int)hipErrorInvalidValue;
     if (workers < a.n_tiles && workers <= kBlock) return (int)hipErrorInvalidValue;   // device holds too few workgroups
-    int lanes = kTicketLanes;
-    if (lanes > 1 && workers / (2 * kBlock) < lanes) lanes = workers / (2 * kBlock) < 1 ? 1 : workers / (2 * kBlock);
-    a.n_lanes = lanes;
     a.n_server_wgs = server_wgs;
     a.n_servers = server_wgs * kWaves;
-    const int32_t n_groups = (a.n_blocks + kBatch - 1) / kBatch;         // groups of kBlock tickets
-    a.lane_tickets = ((n_groups + lanes - 1) / lanes) * kBlock;
+    a.n_tickets = ((a.n_blocks + kBatch - 1) / kBatch) * kBlock;
     // header, tile words and block words are one array
     const int64_t n_words = (int64_t)(kWsHeaderBytes / sizeof(u64)) + a.n_tiles + a.n_blocks;
     int reset_blocks = (int)((n_words + 1023) / 1024);
@@ -1109,11 +1283,16 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
     return (int)hipGetLastError();
 }
 
-int launch_apply(const BucketDev &b, int32_t n_tensors, void *const *dst_ptrs, void *stream) {
+int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
+                 void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int64_t chunks = (b.capacity + kApplyChunk - 1) / kApplyChunk;
-    int blocks = chunks < 1 ? 1 : (chunks > 256 * 16 ? 256 * 16 : (int)chunks);
-    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, dst_ptrs);
+    int64_t chunks = (b.capacity + kApplyThreads - 1) / kApplyThreads;
+    int blocks = chunks < 1 ? 1 : (chunks > 256 * 32 ? 256 * 32 : (int)chunks);
+#ifdef ROSE_APPLY_SCATTER
+    hipLaunchKernelGGL(apply_scatter_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, dst_ptrs);
+#else
+    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs);
+#endif
     return (int)hipGetLastError();
 }
 

@@ -76,9 +76,8 @@ struct EncodeArgs {
     int32_t tp;
     int32_t n_server_wgs;                   // workgroups 0 .. n_server_wgs-1 serve prefixes, the rest walk tiles
     int32_t n_servers;                      // waves that serve prefixes (kWaves per serving workgroup)
-    int32_t lane_tickets;                   // tickets each ticket counter hands out
-    int32_t n_lanes;                        // ticket counters in use (<= kTicketLanes)
-    unsigned int *ticket;                   // workspace header: kTicketLanes counters, kTicketStride bytes apart
+    int32_t n_tickets;                      // tickets the counter hands out
+    unsigned int *ticket;                   // workspace header: the ticket counter
 };
 
 // Tiles of one chain are grouped in blocks of kBlock; a serving wave gathers a block's counts
@@ -86,23 +85,17 @@ struct EncodeArgs {
 constexpr int kBlock = 64;
 
 // workspace layout (bytes): header, tile descriptors, block descriptors
-// A ticket hands a worker kBatch tiles: the tiles at one position of kBatch consecutive blocks.
-// Tickets come from kTicketLanes counters, each serving every kTicketLanes-th group of kBlock
-// tickets, so that the atomics spread over several memory channels.
+// A ticket hands a worker kBatch tiles: the tiles at one position of kBatch consecutive blocks
+// (a "group" of blocks has kBlock tickets).  All tickets come from one counter, in order.
 #ifndef ROSE_BATCH
 #define ROSE_BATCH 3
 #endif
-#ifndef ROSE_TICKET_LANES
-#define ROSE_TICKET_LANES 1
-#endif
 constexpr int kBatch = ROSE_BATCH;
-constexpr int kTicketLanes = ROSE_TICKET_LANES;
-constexpr size_t kTicketStride = 4096;
-static_assert(kTicketLanes >= 1 && kTicketLanes < 32, "ticket lanes are tracked in a 32-bit mask");
 
 constexpr size_t kWsAbortOff = 0;
-constexpr size_t kWsTicketOff = kTicketStride;
-constexpr size_t kWsHeaderBytes = kTicketStride * (1 + kTicketLanes);
+constexpr int kWsCarefulWord = 2;      // 32-bit word 2 of the header counts same-group ticket pairs (diagnostic)
+constexpr size_t kWsTicketOff = 4096;
+constexpr size_t kWsHeaderBytes = 8192;
 
 struct CopyArgs {
     const Piece *pieces;
@@ -121,7 +114,8 @@ inline uint32_t magic_div(uint32_t k, uint32_t magic, uint32_t shift) {
 
 // kernel launchers (kernels.hip); all return a hipError_t as int
 int launch_encode(const EncodeArgs &a, int new_is_f32, void *stream);
-int launch_apply(const BucketDev &b, int32_t n_tensors, void *const *dst_ptrs, void *stream);
+int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
+                 void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
 int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
 
@@ -141,4 +135,5 @@ struct rose_plan {
     mutable int device = -1;
     mutable rose::Piece *d_pieces = nullptr;
     mutable int32_t *d_tile_piece = nullptr;
+    mutable int32_t *d_local_numel = nullptr;  // [n_tensors] elements of a shard's copy of each tensor
 };

@@ -135,6 +135,24 @@ def test_fp32_rounding_special_values():
     assert np.array_equal(want[0]["val"], rb[rb != 0])
 
 
+def test_few_workers_dense_changes(monkeypatch):
+    """Few workers and tiles that fill the LDS ring: workers wait often and take tickets at a low
+    rate, so one worker gets two tickets of one group of blocks in a row; the kernel then
+    publishes that pair's counts before it may wait again.  The result must not depend on any of
+    it.  (Word 2 of the workspace header counts how often the pair handling ran.)"""
+    ts = models.decoder(2, 1024, 16, 16, 64, 2816, 4096, fused=True)
+    pairs = 0
+    for workers, p in [(65, 0.9), (66, 0.6), (70, 0.9), (97, 1.0), (130, 0.3)]:
+        print("case: few workers=%d p=%g seed=%d" % (workers, p, workers), flush=True)
+        monkeypatch.setenv("ROSE_ENCODE_WORKERS", str(workers))
+        c = bern_case(ts, 2, p, seed=workers)
+        full_parity(c, check_dense=False)
+        n = int(c.ws.view(torch.int32)[2])
+        print("  same-group ticket pairs handled: %d" % n, flush=True)
+        pairs += n
+    assert pairs > 0, "the pair handling never ran: the test does not reach what it is for"
+
+
 def test_capacity_overflow_is_reported_and_bounded():
     print("case: capacity overflow", flush=True)
     ts = [T(64, 512, R.SPLIT_ROWS), T(1, 3000, R.REPLICATED)]
