@@ -63,6 +63,15 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
     return x;
 }
 
+// Cache policy of the encode kernel's streams (measured on the 7B workload: both hints together
+// take 0.27 ms off 5.65 ms; either alone gains nothing): the two tensors are read once and the
+// bucket entries are written once, so both are marked non-temporal.
+#ifndef ROSE_NT_LOADS
+#define ROSE_NT_LOADS 1
+#endif
+#ifndef ROSE_NT_STORES
+#define ROSE_NT_STORES 1
+#endif
 // 128-bit load / store through the global address space (pointers fetched from a table would
 // otherwise be treated as generic and use the slower flat instructions)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -71,6 +80,16 @@ __device__ __forceinline__ uint4 gload16(const void *p) {
     u32x4 v = *reinterpret_cast<const global_u32x4 *>(reinterpret_cast<uintptr_t>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+// the same for data that is read once: tells the caches not to keep it
+__device__ __forceinline__ uint4 gload16_stream(const void *p) {
+#if ROSE_NT_LOADS
+    u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const global_u32x4 *>(reinterpret_cast<uintptr_t>(p)));
+#else
+    u32x4 v = *reinterpret_cast<const global_u32x4 *>(reinterpret_cast<uintptr_t>(p));
+#endif
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ void gstore16(void *p, uint4 v) {
     u32x4 w = {v.x, v.y, v.z, v.w};
     *reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(p)) = w;
@@ -240,14 +259,43 @@ __global__ void finalize_kernel(EncodeArgs a) {
     if (threadIdx.x < (unsigned)a.tp && *a.abort_flag) a.bucket[threadIdx.x].seg_off[a.n_tensors] = -1;
 }
 
-#ifndef ROSE_STATS
-#define ROSE_STATS 0          // experiments only: count polls into the workspace header
-#endif
-#if ROSE_STATS
-#define STAT_ADD(a, i, v) atomicAdd(reinterpret_cast<unsigned long long *>(a.abort_flag) + 8 + (i), (unsigned long long)(v))
-#else
-#define STAT_ADD(a, i, v) ((void)0)
-#endif
+// Asking for a ticket without waiting for it.  The counter's answer is in flight from one
+// iteration of the worker loop to the next; a value in flight must not live in a register the
+// compiler knows about (it may copy such a register at any time, before the answer has arrived).
+// So each encode kernel keeps one VGPR out of the compiler's hands (amdgpu_num_vgpr stops the
+// allocator below it) and the two routines here name it directly.
+//   ticket_request: lane 0 of the calling wave adds 1 to *counter; the old value will arrive in
+//                   lane 0 of the reserved register.  Nothing waits.
+//   ticket_take:    waits for every outstanding vector memory operation of the wave, then reads
+//                   the reserved register.
+// The bf16 kernel has 128 registers per lane (4 waves per SIMD), the fp32-master kernel 168 (3).
+#define ROSE_TICKET_VGPR_BF16 "v127"
+#define ROSE_TICKET_VGPR_F32 "v167"
+constexpr int kNumVgprBf16 = 126, kNumVgprF32 = 166;     // what the compiler may use
+template <int NEW_F32>
+__device__ __forceinline__ void ticket_request(unsigned int *counter) {
+    unsigned long long saved;
+    const unsigned int zero = 0, one = 1;
+    if constexpr (NEW_F32)
+        asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add " ROSE_TICKET_VGPR_F32
+                     ", %1, %2, %3 sc0\n\ts_mov_b64 exec, %0"
+                     : "=&s"(saved) : "v"(zero), "v"(one), "s"(counter) : "memory", ROSE_TICKET_VGPR_F32);
+    else
+        asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add " ROSE_TICKET_VGPR_BF16
+                     ", %1, %2, %3 sc0\n\ts_mov_b64 exec, %0"
+                     : "=&s"(saved) : "v"(zero), "v"(one), "s"(counter) : "memory", ROSE_TICKET_VGPR_BF16);
+}
+template <int NEW_F32>
+__device__ __forceinline__ unsigned int ticket_take() {
+    unsigned int t;
+    if constexpr (NEW_F32)
+        asm volatile("s_waitcnt vmcnt(0)\n\tv_mov_b32 %0, " ROSE_TICKET_VGPR_F32 : "=v"(t) : : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)\n\tv_mov_b32 %0, " ROSE_TICKET_VGPR_BF16 : "=v"(t) : : "memory");
+    return t;
+}
+
+__device__ __forceinline__ bool has_prefix(u64 word) { return (word >> kStatusShift) == kStatusPrefix; }
 
 // bounded wait bookkeeping; returns false when the wave must stop waiting
 __device__ __forceinline__ bool keep_waiting(unsigned int *abort_flag, unsigned int &spins, int lane) {
@@ -360,7 +408,6 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 #endif
 constexpr int kRing = ROSE_RING;        // entries parked per workgroup (power of two)
 constexpr int kQueue = ROSE_QUEUE;      // tiles parked per workgroup (<= 64)
-constexpr u64 kUnknown = ~0ull;
 static_assert((kRing & (kRing - 1)) == 0 && (kQueue & (kQueue - 1)) == 0 && kQueue <= 64,
               "ring and queue sizes must be powers of two, the queue at most a wave");
 
@@ -384,14 +431,82 @@ __device__ __forceinline__ TileCtx tile_ctx(const EncodeArgs &a, int32_t tile) {
     c.k_tile = (uint32_t)(tile - c.pc.first_tile) * (uint32_t)kTile;
     c.limit = (c.k_tile + (uint32_t)kTile <= (uint32_t)c.pc.len) ? 0xFFFFFFFFu : (uint32_t)c.pc.len;
     // uniform choice: aligned piece and aligned tensors -> 128-bit loads
-    c.vec = ((c.pc.flags & kPieceVec) && ((((uintptr_t)c.old_base) | ((uintptr_t)c.new_base)) & 15u) == 0) ? 1u : 0u;
+    c.vec = ((c.pc.flags & kPieceVec) && ((((uintptr_t)c.old_base) | ((uintptr_t)c.new_base)) & 15u) == 0 &&
+             c.k_tile + (uint32_t)kVec <= (uint32_t)c.pc.len) ? 1u : 0u;
     c.pad = 0;
     return c;
+}
+
+// What a worker keeps of a tile while it handles it (uniform, a few scalars: the full context is
+// only needed to issue the loads and in rare paths, which build it again).
+struct TileMeta {
+    uint32_t out_base;  // local index of the tile's first element
+    int32_t shard;
+    int32_t seg;        // tensor whose segment starts with this tile, else -1
+    uint32_t limit;     // see load_raw
+    uint32_t vec;
+    uint32_t k_tile;
+};
+__device__ __forceinline__ TileMeta tile_meta(const TileCtx &c, int32_t tile) {
+    TileMeta m;
+    m.out_base = (uint32_t)c.pc.local_base + c.k_tile;
+    m.shard = c.pc.shard;
+    m.seg = ((c.pc.flags & kPieceFirst) && tile == c.pc.first_tile) ? c.pc.tensor : -1;
+    m.limit = c.limit;
+    m.vec = c.vec;
+    m.k_tile = c.k_tile;
+    return m;
+}
+
+// Issue a tile's 128-bit loads of the old and the new tensor: both use the same element offsets,
+// which are worked out once.  t_off = wave * kWaveSpan + lane * kVec.
+template <int NEW_F32>
+__device__ __forceinline__ void raw_zero(int j, RawTile<0> &ro, RawTile<NEW_F32> &rn) {
+    ro.v[j] = make_uint4(0, 0, 0, 0);
+    if constexpr (NEW_F32) rn.lo[j] = rn.hi[j] = make_uint4(0, 0, 0, 0);
+    else rn.v[j] = make_uint4(0, 0, 0, 0);
+}
+// one vector of the old and of the new tensor at element `off` from uniform bases (typed pointer
+// plus a 32-bit offset: the form that needs no 64-bit address arithmetic per lane)
+template <int NEW_F32, typename OFF>
+__device__ __forceinline__ void load_raw_at(const uint16_t *o, const void *n, OFF off, int j, RawTile<0> &ro,
+                                            RawTile<NEW_F32> &rn) {
+    ro.v[j] = gload16_stream(o + off);
+    if constexpr (NEW_F32) {
+        rn.lo[j] = gload16_stream(static_cast<const uint32_t *>(n) + off);
+        rn.hi[j] = gload16_stream(static_cast<const uint32_t *>(n) + off + 4);
+    } else {
+        rn.v[j] = gload16_stream(static_cast<const uint16_t *>(n) + off);
+    }
+}
+// All of a tile's loads are issued unconditionally (no zeroing, no predication: nothing but the
+// loads themselves ever writes the load registers).  A vector that does not fit entirely inside
+// the piece is loaded from the tile's first vector instead, which tile_ctx guarantees to exist
+// for a tile with vec set; the caller discards such vectors.
+template <int NEW_F32>
+__device__ __forceinline__ void load_raw_pair(const TileCtx &c, uint32_t t_off, RawTile<0> &ro, RawTile<NEW_F32> &rn) {
+    const bool full = c.limit == 0xFFFFFFFFu;
+    // One instruction sequence for both kinds of piece: a contiguous piece is walked as a strided
+    // one whose row number is always 0 (magic 0).
+    const bool strided = (c.pc.flags & kPieceStrided) != 0;
+    const uint32_t magic = strided ? c.pc.magic : 0u, shift = strided ? c.pc.shift : 0u;
+    const uint32_t run = strided ? (uint32_t)c.pc.run : 0u;
+    const int64_t stride = strided ? c.pc.stride : 0;
+#pragma unroll
+    for (int j = 0; j < kIters; ++j) {
+        uint32_t k = c.k_tile + t_off + (uint32_t)j * 64 * kVec;
+        if (!full && k + kVec > c.limit) k = c.k_tile;
+        const uint32_t q = __umulhi(k, magic) >> shift;
+        const int64_t e = c.pc.src_off + (int64_t)q * stride + (k - q * run);
+        load_raw_at<NEW_F32>(c.old_base, c.new_base, e, j, ro, rn);
+    }
 }
 
 // Tile at position (ticket mod kBlock) of block (ticket / kBlock) * kBatch + j, or -1 if that block
 // does not exist or is a chain's short last block without that position.  Uniform.
 __device__ __forceinline__ int32_t ticket_tile(const EncodeArgs &a, int32_t ticket, int32_t j) {
+    ticket = __builtin_amdgcn_readfirstlane(ticket);    // uniform anyway: keeps the table look-ups scalar
+    j = __builtin_amdgcn_readfirstlane(j);
     const int32_t blk = (ticket / kBlock) * kBatch + j;
     if (blk >= a.n_blocks) return -1;
     int32_t shard = 0;
@@ -480,41 +595,64 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
     // Uniform bookkeeping, kept identical in every thread.  The queue is a circular FIFO whose i-th
     // oldest tile sits in slot (q_head + i) mod kQueue; the ring holds their entries in that order.
-    // What one iteration copies out stays reserved ("held") until the next iteration's barrier,
-    // because slower threads may still be reading it.
-#if ROSE_STATS
-    unsigned long long st_iters = 0, st_drains = 0, st_spins = 0, st_async = 0, st_drain_clk = 0, st_clk0 = wall_clock64();
-#endif
-    int q_head = 0, q_len = 0, q_held = 0;
-    uint32_t ring_used = 0, ring_held = 0, ring_head = 0;
+    //
+    // Order of the memory operations of one iteration.  The hardware counts outstanding vector
+    // memory operations in issue order, and the compiler can only wait for "all but the newest
+    // n" with an n it can count at compile time; behind loops and branches it has to wait for
+    // everything.  So results are taken in only at the top of an iteration, where everything in
+    // flight is wanted anyway, and the long-latency loads of the next tile are issued after the
+    // iteration's other memory operations (bucket stores, the poll, the ticket request):
+    //   top   the tile's data has landed; so have last iteration's poll answers and ticket
+    //   (a)   change masks of this tile (frees the load registers)
+    //   (b)   copy out the parked tiles announced at the last barrier; wave 0 takes in the poll
+    //         answers and announces (through LDS, valid after this iteration's barrier) which
+    //         parked tiles can be copied out next time
+    //   (c)   wave 0 polls the parked tiles without a prefix; thread 0 asks for a ticket
+    //   (d)   the NEXT tile's loads are issued
+    //   (e)   scan, barrier, publish this tile's count, park its entries (LDS only)
+    int q_head = 0, q_len = 0;
+    uint32_t ring_used = 0, ring_head = 0;
     int parity = 0;
+    int n_announced = 0;        // oldest parked tiles whose prefixes lie in s_excl[parity ^ 1]
     // wave 0 only: lane i tracks the i-th oldest parked tile
     int32_t wq_tile = 0;
-    u64 wq_e = kUnknown;        // its exclusive prefix once known
-    u64 polled = 0;             // answer of the poll issued at the end of the previous iteration
-    bool poll_out = false;
+    u64 wq_w = 0;               // the newest copy of its descriptor word: the prefix once the status says so
+    u64 polled = 0;             // written only by the poll's load (in flight across the iteration boundary)
+    int n_polled = 0;           // lanes of wave 0 whose tiles the poll in flight covers
+    bool ticket_out = false;    // a ticket has been asked for and not yet taken in
 
     // copy the n oldest parked tiles to the buckets (prefixes in excl[0..n)); returns ring entries freed
     auto copy_out = [&](int n, const u64 *excl_by_age, bool ok) -> uint32_t {
         uint32_t freed = 0;
         for (int i = 0; i < n; ++i) {
             const int slot = (q_head + i) & (kQueue - 1);
-            const uint32_t cnt = s_q_count[slot];
+            // everything about the tile is uniform: kept in scalar registers, the bucket's
+            // pointers come through scalar loads
+            const uint32_t cnt = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_count[slot]);
             freed += cnt;
             if (ok && !(ROSE_DIAG & 2)) {
-                const u64 excl = excl_by_age[i];
-                const uint32_t off = s_q_off[slot], base = s_q_base[slot];
-                const BucketDev b = a.bucket[s_q_shard[slot]];
+                const u64 excl = ((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(excl_by_age[i] >> 32)) << 32) |
+                                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)excl_by_age[i]);
+                const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_off[slot]);
+                const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_base[slot]);
+                const BucketDev b = a.bucket[__builtin_amdgcn_readfirstlane(s_q_shard[slot])];
+                const int32_t seg = __builtin_amdgcn_readfirstlane(s_q_seg[slot]);
+                const int32_t last = __builtin_amdgcn_readfirstlane(s_q_last[slot]);
                 if (threadIdx.x == 0) {
-                    if (s_q_seg[slot] >= 0) b.seg_off[s_q_seg[slot]] = (int64_t)excl;
-                    if (s_q_last[slot]) b.seg_off[a.n_tensors] = (int64_t)(excl + cnt);
+                    if (seg >= 0) b.seg_off[seg] = (int64_t)excl;
+                    if (last) b.seg_off[a.n_tensors] = (int64_t)(excl + cnt);
                 }
                 for (uint32_t k = threadIdx.x; k < cnt; k += kThreads) {
                     const u64 pos = excl + k;
                     if (pos < (u64)b.capacity) {
                         const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
+#if ROSE_NT_STORES
+                        __builtin_nontemporal_store((int32_t)(base + (entry >> 16)), b.idx + pos);
+                        __builtin_nontemporal_store((uint16_t)entry, b.val + pos);
+#else
                         b.idx[pos] = (int32_t)(base + (entry >> 16));
                         b.val[pos] = (uint16_t)entry;
+#endif
                     }
                 }
             }
@@ -526,34 +664,25 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         q_len -= n;
         if (wave == 0) {
             wq_tile = __shfl(wq_tile, lane + n, 64);
-            wq_e = __shfl(wq_e, lane + n, 64);
+            wq_w = __shfl(wq_w, lane + n, 64);
         }
     };
 
     // Blocking drain, for when there is no room to park (or at the end): waits until the oldest
-    // parked tile (all = false) or every parked tile (all = true) has its prefix.
+    // parked tile (all = false) or every parked tile (all = true) has its prefix, and copies out
+    // every leading tile whose prefix is known; these include the announced ones.
     auto drain = [&](bool all) {
-#if ROSE_STATS
-        const unsigned long long st_t0 = wall_clock64();
-        ++st_drains;
-#endif
         __syncthreads();                               // parked entries visible; earlier copies done
-        ring_used -= ring_held;
-        ring_held = 0;
-        q_held = 0;
         if (wave == 0) {
             bool ok = true;
             int n_ready = q_len;
 #if !(ROSE_DIAG & 1)
             unsigned int spins = 0;
             for (;;) {
-                if (lane < q_len && wq_e == kUnknown) {
-                    u64 v = desc_load(a.tile_desc + wq_tile);
-                    if ((v >> kStatusShift) == kStatusPrefix) wq_e = v & kValueMask;
-                }
-                const u64 unknown = __ballot(lane < q_len && wq_e == kUnknown);
+                if (lane < q_len && !has_prefix(wq_w)) wq_w = desc_load(a.tile_desc + wq_tile);
+                const u64 unknown = __ballot(lane < q_len && !has_prefix(wq_w));
                 n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
-                if (all ? (n_ready == q_len) : (n_ready >= 1 || q_len == 0)) break;   // q_len 0: only held space was needed
+                if (all ? (n_ready == q_len) : (n_ready >= 1 || q_len == 0)) break;
                 if (!keep_waiting(a.abort_flag, spins, lane)) {
                     ok = false;         // give up: drop everything that is parked
                     n_ready = q_len;
@@ -561,9 +690,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 }
             }
 #else
-            wq_e = 0;
+            wq_w = kStatusPrefix << kStatusShift;
 #endif
-            if (lane < n_ready) s_excl_sync[lane] = wq_e;
+            if (lane < n_ready) s_excl_sync[lane] = wq_w & kValueMask;
             if (lane == 0) {
                 s_ok = ok ? 1 : 0;
                 s_ready = n_ready;
@@ -575,16 +704,13 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         __syncthreads();                               // ring and queue slots may be reused
         pop(n_ready);
         ring_used -= freed;
-#if ROSE_STATS
-        st_drain_clk += wall_clock64() - st_t0;
-#endif
+        n_announced = 0;
+        n_polled = 0;                                  // the lanes of wave 0 have moved
     };
 
-    // Tiles come from tickets (dynamic, so that faster workgroups take more): a ticket is fetched
-    // one tile ahead by thread 0 and handed to the others through LDS at the next barrier.
-    auto fetch_ticket = [&]() -> unsigned int {
-        return __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
+    // Tiles come from tickets (dynamic, so that faster workgroups take more): thread 0 asks for a
+    // ticket well before it is needed; the answer is handed to the others through LDS at the
+    // barrier of the following iteration.
     Walk walk;
     walk.ticket = -1;
     walk.j = kBatch;
@@ -594,15 +720,21 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     walk.exhausted = false;
     walk.careful = false;
     walk.redo = false;
-    auto fetch_ticket_now = [&]() {        // all threads; two barriers; no waiting
-        if (threadIdx.x == 0) s_ticket_sync = (int32_t)fetch_ticket();
+    // all threads; two barriers; no waiting for other workgroups.  Takes in the ticket that is on
+    // its way, if any, else asks for one.
+    auto settle_ticket = [&]() {
+        if (threadIdx.x == 0) {
+            if (!ticket_out) ticket_request<NEW_F32>(a.ticket);
+            s_ticket_sync = (int32_t)ticket_take<NEW_F32>();
+        }
+        ticket_out = false;
         __syncthreads();
         walk_accept(a, walk, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket_sync));
         __syncthreads();
     };
     // Count-only pass over one tile (all threads, rolled loads: this is rare): publishes its count.
     auto publish_count = [&](int32_t t) {
-        const TileCtx c = tile_ctx(a, t);
+        const TileCtx c = tile_ctx(a, __builtin_amdgcn_readfirstlane(t));
         uint32_t cnt = 0;
 #pragma unroll 1
         for (int j = 0; j < kIters; ++j) {
@@ -626,42 +758,83 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         const int st = walk_step(a, walk, &tile);
         if (st == kWalkTile) break;
         if (st == kWalkDone) return;
-        fetch_ticket_now();
+        settle_ticket();
     }
     walk.careful = false;                              // nothing is parked yet, nothing has waited
     bool cur_redo = false;
-    TileCtx cur = tile_ctx(a, tile);
+    const uint32_t t_off = (uint32_t)wave * kWaveSpan + (uint32_t)lane * kVec;
     RawTile<0> raw_old;
     RawTile<NEW_F32> raw_new;
-    if (cur.vec) {
-        const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
-        load_raw(cur.old_base, cur.pc, k_wave, lane, cur.limit, raw_old);
-        load_raw(cur.new_base, cur.pc, k_wave, lane, cur.limit, raw_new);
-    }
+#pragma unroll
+    for (int j = 0; j < kIters; ++j) raw_zero(j, raw_old, raw_new);
+    // the tile's context, its loads (if 128-bit loads are legal for it), and what is kept of it
+    auto start_tile = [&](int32_t t) -> TileMeta {
+        const TileCtx c = tile_ctx(a, __builtin_amdgcn_readfirstlane(t));
+        if (c.vec) load_raw_pair<NEW_F32>(c, t_off, raw_old, raw_new);
+        return tile_meta(c, t);
+    };
+    TileMeta cur, nxt;
+    bool loaded = false;                               // the tile's loads have been issued
 
     for (;;) {
-        // ask for the next ticket as soon as the one fetched ahead has been taken into use
-        const bool request = !walk.have_next && !walk.exhausted && !walk.redo;
-        unsigned int pending_ticket = 0;
-        if (request && threadIdx.x == 0) pending_ticket = fetch_ticket();
-
-        const Piece pc = cur.pc;
+        // All of the following are the same in every lane; saying so keeps them, and everything
+        // derived from them, in scalar registers.
+        tile = __builtin_amdgcn_readfirstlane(tile);
+        q_head = __builtin_amdgcn_readfirstlane(q_head);
+        q_len = __builtin_amdgcn_readfirstlane(q_len);
+        ring_used = (uint32_t)__builtin_amdgcn_readfirstlane((int)ring_used);
+        ring_head = (uint32_t)__builtin_amdgcn_readfirstlane((int)ring_head);
+        parity = __builtin_amdgcn_readfirstlane(parity);
+        n_announced = __builtin_amdgcn_readfirstlane(n_announced);
+        n_polled = __builtin_amdgcn_readfirstlane(n_polled);
+        walk.ticket = __builtin_amdgcn_readfirstlane(walk.ticket);
+        walk.j = __builtin_amdgcn_readfirstlane(walk.j);
+        walk.next_ticket = __builtin_amdgcn_readfirstlane(walk.next_ticket);
+        walk.redo_through = __builtin_amdgcn_readfirstlane(walk.redo_through);
+        {
+            const int flags = __builtin_amdgcn_readfirstlane((int)loaded | (int)cur_redo << 1 | (int)ticket_out << 2 |
+                                                             (int)walk.have_next << 3 | (int)walk.exhausted << 4 |
+                                                             (int)walk.careful << 5 | (int)walk.redo << 6);
+            loaded = flags & 1;
+            cur_redo = flags & 2;
+            ticket_out = flags & 4;
+            walk.have_next = flags & 8;
+            walk.exhausted = flags & 16;
+            walk.careful = flags & 32;
+            walk.redo = flags & 64;
+        }
+        cur = loaded ? nxt : start_tile(tile);         // not loaded: the first tile, or one named late
+        // ---- (a) change masks ----
         const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
         uint4 nv[kIters];
         uint32_t mask[kIters];
-        if (cur.vec) {
+        // Always taken from the load registers, also for a tile that has no 128-bit loads (its
+        // result is replaced below): this way every path consumes what was loaded, and the
+        // compiler never has to wait for memory before the registers are loaded again.
 #pragma unroll
-            for (int j = 0; j < kIters; ++j) {
-                nv[j] = raw_to_bf16(raw_new, j);
-                mask[j] = nz16_mask(xor4(raw_old.v[j], nv[j]));
+        for (int j = 0; j < kIters; ++j) {
+            nv[j] = raw_to_bf16(raw_new, j);
+            mask[j] = nz16_mask(xor4(raw_old.v[j], nv[j]));
+        }
+        // pin the above here: the load registers are dead from this point on, whatever the
+        // scheduler would prefer
+#pragma unroll
+        for (int j = 0; j < kIters; ++j)
+            asm volatile("" : "+v"(mask[j]), "+v"(nv[j].x), "+v"(nv[j].y), "+v"(nv[j].z), "+v"(nv[j].w));
+        if (cur.vec) {
+            if (cur.limit != 0xFFFFFFFFu) {            // vectors past the end of the piece hold nothing
+#pragma unroll
+                for (int j = 0; j < kIters; ++j)
+                    if (k_wave + (uint32_t)(j * 64 + lane) * kVec + kVec > cur.limit) mask[j] = 0;
             }
             // a piece whose length is not a multiple of 8: the one vector that straddles its end
             if (cur.limit != 0xFFFFFFFFu && (cur.limit & (kVec - 1))) {
                 const uint32_t ks = cur.limit & ~(uint32_t)(kVec - 1);
+                const TileCtx c = tile_ctx(a, __builtin_amdgcn_readfirstlane(tile));
                 if (ks >= k_wave && ks < k_wave + (uint32_t)kWaveSpan && ((ks - k_wave) / kVec) % 64 == (uint32_t)lane) {
                     const uint32_t js = (ks - k_wave) / (64 * kVec);
-                    uint4 o = load_vec_general<0>(cur.old_base, pc, ks);
-                    uint4 n = load_vec_general<NEW_F32>(cur.new_base, pc, ks);
+                    uint4 o = load_vec_general<0>(c.old_base, c.pc, ks);
+                    uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, ks);
                     uint32_t m = nz16_mask(xor4(o, n));
 #pragma unroll
                     for (int jj = 0; jj < kIters; ++jj) {
@@ -676,11 +849,12 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             // shapes or pointers that are not multiples of 16 bytes.  Kept as a rolled loop (one
             // vector in flight) so that this rare path does not set the kernel's register budget;
             // the selects put the result into static slots
+            const TileCtx c = tile_ctx(a, __builtin_amdgcn_readfirstlane(tile));
 #pragma unroll 1
             for (int j = 0; j < kIters; ++j) {
                 uint32_t k = k_wave + (uint32_t)(j * 64 + lane) * kVec;
-                uint4 o = load_vec_general<0>(cur.old_base, pc, k);
-                uint4 n = load_vec_general<NEW_F32>(cur.new_base, pc, k);
+                uint4 o = load_vec_general<0>(c.old_base, c.pc, k);
+                uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, k);
                 uint32_t m = nz16_mask(xor4(o, n));
 #pragma unroll
                 for (int jj = 0; jj < kIters; ++jj) {
@@ -692,22 +866,47 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             }
         }
 
-        // the next tile's loads go out now and stay in flight during everything below
-        int32_t next = -1;
-        int next_state = walk_step(a, walk, &next);     // kWalkNeedTicket: decided after the barrier
-        bool nxt_redo = walk.redo;
-        TileCtx nxt = cur;
-        if (next_state == kWalkTile) {
-            nxt = tile_ctx(a, next);
-            if (nxt.vec) {
-                const uint32_t kw = nxt.k_tile + (uint32_t)wave * kWaveSpan;
-                load_raw(nxt.old_base, nxt.pc, kw, lane, nxt.limit, raw_old);
-                load_raw(nxt.new_base, nxt.pc, kw, lane, nxt.limit, raw_new);
-            }
+        // ---- (b) poll answers and ticket of the previous iteration; copy out what was announced ----
+        const bool accept_now = ticket_out;
+        if (accept_now && threadIdx.x == 0) {
+            s_ticket[parity] = (int32_t)ticket_take<NEW_F32>();   // nothing else is in flight here
+        }
+        ticket_out = false;
+        if (wave == 0 && lane < n_polled && !has_prefix(wq_w)) wq_w = polled;
+#if ROSE_DIAG & 1
+        wq_w = kStatusPrefix << kStatusShift;
+#endif
+        if (n_announced > 0) {
+            ring_used -= copy_out(n_announced, s_excl[parity ^ 1], true);
+            pop(n_announced);
+            n_announced = 0;
+        }
+        if (wave == 0) {
+            const u64 unknown = __ballot(lane < q_len && !has_prefix(wq_w));
+            const int n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
+            if (lane < n_ready) s_excl[parity][lane] = wq_w & kValueMask;
+            if (lane == 0) s_nready[parity] = n_ready;
+            // ---- (c) poll: one lane per parked tile that has no prefix yet ----
+            if (lane < q_len && !has_prefix(wq_w)) polled = desc_load(a.tile_desc + wq_tile);
+        }
+        n_polled = q_len;
+        // ask for the next ticket as soon as the one fetched ahead has been taken into use
+        if (!walk.have_next && !accept_now && !walk.exhausted && !walk.redo) {
+            if (threadIdx.x == 0) ticket_request<NEW_F32>(a.ticket);
+            ticket_out = true;
         }
 
-        // exclusive rank of each of this lane's vectors inside the wave's span: the per-vector
-        // counts (<= 8, wave totals <= 512) are scanned two at a time in 16-bit fields
+        // ---- (d) the next tile's loads go out now and stay in flight during everything below ----
+        int32_t next = -1;
+        int next_state = walk_step(a, walk, &next);     // kWalkNeedTicket: decided after the barrier
+        next_state = __builtin_amdgcn_readfirstlane(next_state);   // uniform anyway: scalar branches below
+        next = __builtin_amdgcn_readfirstlane(next);
+        bool nxt_redo = walk.redo;
+        loaded = next_state == kWalkTile;
+        if (loaded) nxt = start_tile(next);
+
+        // ---- (e) exclusive rank of each of this lane's vectors inside the wave's span: the
+        // per-vector counts (<= 8, wave totals <= 512) are scanned two at a time in 16-bit fields
         uint32_t rank[kIters];
         uint32_t wave_total = 0;
 #pragma unroll
@@ -724,23 +923,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             }
         }
         if (lane == 0) s_wave_total[parity][wave] = wave_total;
-        if (request && threadIdx.x == 0) s_ticket[parity] = (int32_t)pending_ticket;
-        // wave 0 takes in the answers of the poll it sent at the end of the previous iteration
-        // (they arrived long ago) and tells everyone how many of the oldest tiles are ready
-        if (wave == 0) {
-#if !(ROSE_DIAG & 1)
-            if (poll_out && lane < q_len && wq_e == kUnknown && (polled >> kStatusShift) == kStatusPrefix)
-                wq_e = polled & kValueMask;
-#else
-            wq_e = 0;
-#endif
-            const u64 unknown = __ballot(lane < q_len && wq_e == kUnknown);
-            const int n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
-            if (lane < n_ready) s_excl[parity][lane] = wq_e;
-            if (lane == 0) s_nready[parity] = n_ready;
-        }
         __syncthreads();
-        if (request) walk_accept(a, walk, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket[parity]));
+        if (accept_now) walk_accept(a, walk, (uint32_t)__builtin_amdgcn_readfirstlane(s_ticket[parity]));
+        n_announced = __builtin_amdgcn_readfirstlane(s_nready[parity]);
         uint32_t wave_excl = 0, tile_total = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
@@ -748,42 +933,30 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             if (w < wave) wave_excl += c;
             tile_total += c;
         }
+        tile_total = (uint32_t)__builtin_amdgcn_readfirstlane((int)tile_total);   // uniform: scalar bookkeeping below
+        parity ^= 1;
 
         // publish the count: a serving wave turns it into this tile's prefix
         if (threadIdx.x == 0 && !cur_redo && !(ROSE_DIAG & 4))
             desc_store(a.tile_desc + tile, (kStatusAggregate << kStatusShift) | tile_total);
 
-        // what the previous iteration copied out is free now (everyone has passed the barrier)
-        ring_used -= ring_held;
-        ring_held = 0;
-        q_held = 0;
-        {   // copy out the parked tiles whose prefixes have arrived; their space is held one round
-            const int n_ready = __builtin_amdgcn_readfirstlane(s_nready[parity]);
-#if ROSE_STATS
-            ++st_iters;
-            st_async += n_ready;
-#endif
-            if (n_ready > 0) {
-                ring_held = copy_out(n_ready, s_excl[parity], true);
-                q_held = n_ready;
-                pop(n_ready);
-            }
-        }
-        parity ^= 1;
-
+        // Room to park?  Making room may wait, and nothing may wait while a ticket is on its way
+        // (it could be of the current ticket's group): take it in first.
+        const bool big = tile_total > (uint32_t)kRing;
+        if (ticket_out && !walk.careful && (big || q_len == kQueue || ring_used + tile_total > (uint32_t)kRing))
+            settle_ticket();
         // A same-group ticket has just been accepted: nothing may wait now.  This tile is not
         // parked; it is walked again after the count-only pass at the end of the iteration.
         const bool skip = walk.careful;
-        const bool big = tile_total > (uint32_t)kRing;
         if (skip) {
         } else if (big) {
             if (q_len > 0) drain(true);
         } else {
-            while (q_len + q_held == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
+            while (q_len == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
         }
 
-        const int32_t chain_last = a.chain_first[pc.shard + 1] - 1;
-        const int32_t seg = ((pc.flags & kPieceFirst) && tile == pc.first_tile) ? pc.tensor : -1;
+        const int32_t chain_last = a.chain_first[cur.shard + 1] - 1;
+        const int32_t seg = cur.seg;
         if (skip) {
         } else if (!big) {
             // park the entries: ring slot = ring_head + rank inside the tile
@@ -792,7 +965,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             for (int j = 0; j < kIters; ++j) {
                 uint32_t m = mask[j];
                 uint32_t slot = base + rank[j];
-                const uint32_t in_tile0 = (uint32_t)wave * kWaveSpan + (uint32_t)(j * 64 + lane) * kVec;
+                const uint32_t in_tile0 = t_off + (uint32_t)(j * 64) * kVec;
                 while (m && !(ROSE_DIAG & 8)) {
                     const uint32_t e = __ffs(m) - 1;
                     m &= m - 1;
@@ -804,14 +977,14 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 const int slot = (q_head + q_len) & (kQueue - 1);
                 s_q_count[slot] = tile_total;
                 s_q_off[slot] = ring_head;
-                s_q_base[slot] = (uint32_t)pc.local_base + cur.k_tile;
-                s_q_shard[slot] = pc.shard;
+                s_q_base[slot] = cur.out_base;
+                s_q_shard[slot] = cur.shard;
                 s_q_seg[slot] = seg;
                 s_q_last[slot] = tile == chain_last;
             }
             if (wave == 0 && lane == q_len) {
                 wq_tile = tile;
-                wq_e = kUnknown;
+                wq_w = 0;
             }
             ++q_len;
             ring_used += tile_total;
@@ -842,7 +1015,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             }
             __syncthreads();
             const u64 tile_excl = s_direct_excl;
-            const BucketDev b = a.bucket[pc.shard];
+            const BucketDev b = a.bucket[cur.shard];
             if (s_ok && !(ROSE_DIAG & 2)) {
                 if (threadIdx.x == 0) {
                     if (seg >= 0) b.seg_off[seg] = (int64_t)tile_excl;
@@ -853,7 +1026,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 for (int j = 0; j < kIters; ++j) {
                     uint32_t m = mask[j];
                     u64 pos = wave_base + rank[j];
-                    const uint32_t local0 = (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec;
+                    const uint32_t local0 = cur.out_base + t_off + (uint32_t)(j * 64) * kVec;
                     while (m) {
                         const uint32_t e = __ffs(m) - 1;
                         m &= m - 1;
@@ -868,13 +1041,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             __syncthreads();                           // s_direct_excl / s_ok are reused
         }
 
-        // send the next poll: one lane per parked tile that has no prefix yet.  The answers are
-        // taken in at the next iteration, after that tile's own data has arrived, so nobody waits.
-        poll_out = q_len > 0;
-        if (wave == 0 && lane < q_len && wq_e == kUnknown) polled = desc_load(a.tile_desc + wq_tile);
-
-        // the rare case that the next tile could not be named before the barrier above: name it
-        // now and issue its loads late
+        // The rare cases that the next tile could not be named before the barrier above, or that a
+        // same-group ticket has arrived: settle them now; the next tile's loads are then issued at
+        // the top of the next iteration.
         bool late = false;
         bool redo_cur = skip;                          // this iteration's tile was not parked
         for (;;) {
@@ -887,12 +1056,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                     for (int32_t j = 0; j < kBatch; ++j)
                         if (ticket_tile(a, tA, j) == tile) j_from = j;
                 redo_cur = false;
-                for (int32_t j = j_from + 1; j < kBatch; ++j) {
-                    const int32_t t = ticket_tile(a, tA, j);
-                    if (t >= 0) publish_count(t);
-                }
-                for (int32_t j = 0; j < kBatch; ++j) {
-                    const int32_t t = ticket_tile(a, tB, j);
+#pragma unroll 1
+                for (int32_t j = j_from + 1; j < 2 * kBatch; ++j) {
+                    const int32_t t = j < kBatch ? ticket_tile(a, tA, j) : ticket_tile(a, tB, j - kBatch);
                     if (t >= 0) publish_count(t);
                 }
                 __syncthreads();
@@ -907,7 +1073,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             }
             if (next_state != kWalkNeedTicket) break;
             if (!walk.have_next && !walk.exhausted) {
-                fetch_ticket_now();
+                settle_ticket();
                 if (walk.careful) continue;
             }
             next_state = walk_step(a, walk, &next);
@@ -915,39 +1081,25 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         }
         if (late) {
             nxt_redo = walk.redo;
-            if (next_state == kWalkTile) {
-                nxt = tile_ctx(a, next);
-                if (nxt.vec) {
-                    const uint32_t kw = nxt.k_tile + (uint32_t)wave * kWaveSpan;
-                    load_raw(nxt.old_base, nxt.pc, kw, lane, nxt.limit, raw_old);
-                    load_raw(nxt.new_base, nxt.pc, kw, lane, nxt.limit, raw_new);
-                }
-            }
+            loaded = false;
         }
         if (next_state == kWalkDone) break;
-        cur = nxt;
         cur_redo = nxt_redo;
         tile = next;
     }
     while (q_len > 0) drain(true);
-#if ROSE_STATS
-    if (threadIdx.x == 0) {
-        unsigned long long *st = a.block_desc + a.n_blocks + (size_t)blockIdx.x * 8;
-        st[0] = st_iters; st[1] = st_drains; st[2] = st_async; st[3] = st_drain_clk; st[4] = wall_clock64() - st_clk0;
-    }
-#endif
 }
 
 // The two instantiations get their own register budgets: 4 waves per SIMD (128 VGPRs) fit the
 // bf16 kernel without spills, the fp32-master kernel holds twice the raw data and gets 3.
 template <int NEW_F32> __global__ void encode_kernel(EncodeArgs a);
 template <>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(ROSE_WAVES_PER_EU, ROSE_WAVES_PER_EU)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4), amdgpu_num_vgpr(kNumVgprBf16)))
 void encode_kernel<0>(EncodeArgs a) {
     encode_body<0>(a);
 }
 template <>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3), amdgpu_num_vgpr(kNumVgprF32)))
 void encode_kernel<1>(EncodeArgs a) {
     encode_body<1>(a);
 }
