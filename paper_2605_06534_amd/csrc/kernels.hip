@@ -1109,8 +1109,10 @@ void encode_kernel<1>(EncodeArgs a) {
 //
 // Scattered 2-byte stores reach memory as byte-masked partial writes of the lines they touch,
 // which the memory side turns into slow read-modify-writes (measured: about 3 TB/s of line
-// traffic).  So the kernel does the read-modify-write itself, one 64-byte line at a time and with
-// 128-bit accesses: a wave takes 64 consecutive entries (ascending local index inside a segment,
+// traffic).  So the kernel does the read-modify-write itself, one 64-byte line at a time, with
+// 128-bit accesses marked non-temporal (a line is touched once per launch; with the hints this
+// path was never slower than direct stores between 1 % and 10 % density, without them it lost
+// below 3 %): a wave takes 64 consecutive entries (ascending local index inside a segment,
 // so the entries of a line are neighbours), finds the distinct lines they touch, loads those lines
 // into LDS, patches the entries in, and stores the lines back whole.
 //
@@ -1121,15 +1123,14 @@ void encode_kernel<1>(EncodeArgs a) {
 // whose size is not a multiple of 8) and entries of tensors that are not 16-byte aligned are stored
 // directly; the line path never touches those bytes.
 // ---------------------------------------------------------------------------------------------
+#ifndef ROSE_APPLY_NT
+#define ROSE_APPLY_NT 14     // non-temporal hints: 1 entry loads, 2 line loads, 4 line stores, 8 direct stores
+                             // (measured best on the 7B workload at 1 - 10 % density)
+#endif
 constexpr int kApplyThreads = 256;
 constexpr int kApplyWaves = kApplyThreads / 64;
 constexpr int kLineElems = 32;                  // 64-byte line of 16-bit elements
 constexpr int kLineShift = 5;
-// a wave rewrites whole lines when its entries average at least NUM / DEN per line
-#ifndef ROSE_APPLY_LINE_NUM
-#define ROSE_APPLY_LINE_NUM 3
-#define ROSE_APPLY_LINE_DEN 2
-#endif
 
 __device__ __forceinline__ void lds_wave_fence() {
     // LDS operations of one wave are carried out in order; this keeps the compiler from moving
@@ -1166,8 +1167,13 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
         const int64_t e = wbase + lane, e2 = e + 64;
         const bool valid = e < total;
         // everything that depends on the entry numbers alone is requested first
+#if ROSE_APPLY_NT & 1
+        const int32_t idx = valid ? __builtin_nontemporal_load(b.idx + e) : 0;
+        const uint32_t val = valid ? __builtin_nontemporal_load(b.val + e) : 0u;
+#else
         const int32_t idx = valid ? b.idx[e] : 0;
         const uint32_t val = valid ? b.val[e] : 0u;
+#endif
         const int32_t idx_before = (lane == 0 && wbase > 0) ? b.idx[wbase - 1] : 0;
         const bool look = lane < kLineElems && e2 < total;
         const int32_t idx2 = look ? b.idx[e2] : 0;
@@ -1212,14 +1218,6 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
         const u64 heads = __ballot(head);
         const int n_lines = __popcll(heads);
         const int slot = __popcll(heads & ((2ull << lane) - 1)) - 1;      // line slot of an owned lane
-        // Few entries per line: rewriting whole lines moves more bytes than it saves, store directly.
-        const int n_owned = __popcll(__ballot(owned)) + __popcll(__ballot(ext));
-        if (n_lines * ROSE_APPLY_LINE_NUM > n_owned * ROSE_APPLY_LINE_DEN) {
-            if (owned || direct) dst[idx] = (uint16_t)val;
-            uint16_t *dst63 = reinterpret_cast<uint16_t *>((uintptr_t)__shfl((u64)(uintptr_t)dst, 63, 64));
-            if (ext) dst63[idx2] = (uint16_t)val2;
-            continue;
-        }
         if (head) {
             const int32_t line_first = (idx >> kLineShift) << kLineShift;
             s_addr[wave][slot] = (u64)(uintptr_t)(dst + line_first);
@@ -1232,7 +1230,11 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
         for (int r = 0; r * 16 < n_lines; ++r) {
             const int sl = r * 16 + (lane >> 2), part = lane & 3;
             if (sl < n_lines && part < s_parts[wave][sl])
+#if ROSE_APPLY_NT & 2
+                s_line[wave][sl][part] = gload16_stream(reinterpret_cast<const char *>((uintptr_t)s_addr[wave][sl]) + part * 16);
+#else
                 s_line[wave][sl][part] = gload16(reinterpret_cast<const char *>((uintptr_t)s_addr[wave][sl]) + part * 16);
+#endif
         }
         lds_wave_fence();
 
@@ -1246,9 +1248,21 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
         for (int r = 0; r * 16 < n_lines; ++r) {
             const int sl = r * 16 + (lane >> 2), part = lane & 3;
             if (sl < n_lines && part < s_parts[wave][sl])
+#if ROSE_APPLY_NT & 4
+                {
+                    const uint4 v4 = s_line[wave][sl][part];
+                    u32x4 w = {v4.x, v4.y, v4.z, v4.w};
+                    __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>((uintptr_t)s_addr[wave][sl] + part * 16));
+                }
+#else
                 gstore16(reinterpret_cast<char *>((uintptr_t)s_addr[wave][sl]) + part * 16, s_line[wave][sl][part]);
+#endif
         }
+#if ROSE_APPLY_NT & 8
+        if (direct) __builtin_nontemporal_store((uint16_t)val, dst + idx);
+#else
         if (direct) dst[idx] = (uint16_t)val;
+#endif
         lds_wave_fence();                               // the LDS slots are reused by the next round
     }
 }
