@@ -136,6 +136,11 @@ rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
  * not arrive within a few seconds the launch is marked as failed, every workgroup still exits,
  * seg_off[n_tensors] of every bucket is set to -1, rose_bucket_check returns ROSE_ERR_HIP and
  * rose_delta_apply of such a bucket does nothing.
+ *
+ * Environment: ROSE_ENCODE_WORKERS=<n> (read at every call) caps the number of workgroups that
+ * walk tiles, e.g. to leave compute units to other kernels; values of 64 or less, or above what
+ * the device holds, are ignored.  After a launch the 32-bit word 2 of the workspace holds a
+ * diagnostic count (how often a workgroup received two tickets of one group of blocks in a row).
  */
 rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs,
                               const void *const *new_ptrs, int32_t new_dtype,
@@ -149,6 +154,10 @@ rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs
  *   dst_ptrs  DEVICE array of n_tensors device pointers to shard d's local tensors
  *             (rose_plan_local_numel elements each, 2-byte aligned at least)
  * Entries at positions >= capacity (an overflowed bucket) are not applied.
+ * The kernel reads and rewrites whole 64-byte pieces of a destination tensor around the entries
+ * it applies (never a byte outside the tensor): nothing else may write the destination tensors
+ * while the call runs.  The first device call on a plan (encode, apply or dense copy) uploads the
+ * plan's tables with hipMalloc / hipMemcpy; later calls allocate nothing.
  */
 rose_status rose_delta_apply(const rose_plan *plan, int32_t d, const rose_bucket *bucket,
                              void *const *dst_ptrs, void *stream);
