@@ -130,6 +130,17 @@ def main():
     t_enc = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps      # ms, HIP events on the launch stream
     t_app = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
 
+    # dense path for comparison (Sec. 6.3 crossover): every shard's slice of the new weights copied
+    ev_c = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for rep in range(3):
+        if rep == 1:
+            ev_c[0].record()
+        for d in range(tp):
+            R.dense_copy(plan, d, new_tab, new_dtype, shard_tabs[d])
+    ev_c[1].record()
+    torch.cuda.synchronize()
+    t_copy = ev_c[0].elapsed_time(ev_c[1]) / 2
+
     in_bytes_per_elem = 6 if new_dtype == R.FP32_RNE else 4
     scanned = in_bytes_per_elem * n_elems
     enc_bytes = scanned + 6 * nnz_total            # algorithmic: read old + new once, write idx + val
@@ -154,6 +165,18 @@ def main():
         probe[name + "_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
     del src, dst
 
+    # Modelled synchronisation time over a link of B Gbit/s (the paper's range): the sparse path sends
+    # 6 bytes per entry, the dense path 2 bytes per element; kernel times are the measured ones.
+    crossover = {}
+    for gbps in (1, 5, 20, 200):
+        bps = gbps * 1e9 / 8
+        crossover["%dGbps" % gbps] = {"sparse_s": round((t_enc + t_app) / 1e3 + 6 * nnz_total / bps, 4),
+                                      "dense_s": round(t_copy / 1e3 + 2 * n_elems / bps, 4)}
+    # apply moves whole 64-byte lines: entries read + touched lines read and written
+    local_elems = sum(plan.local_numel(t, d) for t in range(len(tensors)) for d in range(tp))
+    dens = nnz_total / local_elems
+    app_line_bytes = 6 * nnz_total + 2 * (1 - (1 - dens) ** 32) * 2 * local_elems
+
     out = {
         "metric": "weight-delta encode+apply GB/s (bf16 scanned)",
         "value": round(value, 2),
@@ -175,6 +198,11 @@ def main():
                    "apply_algorithmic_GBs": round(app_bytes / 1e9 / (t_app / 1e3), 1) if t_app > 0 else None,
                    "encode_plus_apply_algorithmic_frac_of_peak":
                        round((enc_bytes + app_bytes) / 1e9 / ((t_enc + t_app) / 1e3) / HBM_PEAK_GBS, 4),
+                   "apply_line_model_bytes": int(app_line_bytes),
+                   "apply_line_model_frac_of_peak": round(app_line_bytes / 1e9 / (t_app / 1e3) / HBM_PEAK_GBS, 4)
+                   if t_app > 0 else None,
+                   "t_dense_copy_ms": round(t_copy, 4), "wire_bytes_sparse_over_dense": round(6 * nnz_total / (2 * n_elems), 4),
+                   "modelled_sync": crossover,
                    "bw_probe": probe, "tiles": plan.n_tiles()},
     }
 
