@@ -163,7 +163,29 @@ def main():
         torch.cuda.synchronize()
         moved = (2 if name == "copy" else 1) * src.numel() * 10
         probe[name + "_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
-    del src, dst
+    # the same mix of reads and writes as the encode launch (two read streams, 6 * nnz / tiles bytes
+    # written per 2 x 16 KB read), with no work attached: what HBM delivers for that traffic
+    if new_dtype == R.BF16:
+        per_chunk = min(16384, max(16, int(round(6 * nnz_total / max(plan.n_tiles(), 1) / 16)) * 16))
+        del src, dst
+        big = 4 << 30                                  # per stream: far beyond the 256 MB memory-side cache
+        src_a = torch.empty(big, dtype=torch.uint8, device=dev).fill_(1)
+        src_b = torch.empty(big, dtype=torch.uint8, device=dev).fill_(2)
+        mix_dst = torch.empty((big // 16384) * per_chunk, dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            R.bw_probe_mixed(src_a, src_b, mix_dst, per_chunk, sink)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            R.bw_probe_mixed(src_a, src_b, mix_dst, per_chunk, sink)
+        b.record()
+        torch.cuda.synchronize()
+        moved = (2 * big + mix_dst.numel()) * 5
+        probe["encode_mix_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
+        probe["encode_mix_write_bytes_per_16k_pair"] = per_chunk
+        del mix_dst, src_a, src_b
+    else:
+        del src, dst
 
     # Modelled synchronisation time over a link of B Gbit/s (the paper's range): the sparse path sends
     # 6 bytes per entry, the dense path 2 bytes per element; kernel times are the measured ones.

@@ -185,6 +185,18 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
  */
 rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
 
+/*
+ * Mixed probe: the memory traffic of a delta_encode launch without its work, to measure what HBM
+ * delivers for that mix of reads and writes.  Reads read_bytes (a multiple of ROSE_PROBE_CHUNK)
+ * from each of src_a and src_b in chunks of ROSE_PROBE_CHUNK bytes and writes
+ * write_bytes_per_chunk (a multiple of 16, at most ROSE_PROBE_CHUNK) per chunk to dst, contiguous
+ * across chunks: dst needs (read_bytes / ROSE_PROBE_CHUNK) * write_bytes_per_chunk bytes.  All
+ * device memory, 16-byte aligned; sink as in rose_bw_probe.
+ */
+#define ROSE_PROBE_CHUNK 16384
+rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
+                                size_t write_bytes_per_chunk, uint64_t *sink, void *stream);
+
 const char *rose_status_str(rose_status s);
 
 #ifdef __cplusplus

@@ -51,6 +51,7 @@ _SIGS = {
     "rose_dense_copy": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp]),
     "rose_bucket_check": (_i32, [_vp, _P(CBucket), _vp, _P(_i64)]),
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
+    "rose_bw_probe_mixed": (_i32, [_vp, _vp, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp]),
     "rose_status_str": (ctypes.c_char_p, [_i32]),
 }
 
@@ -209,3 +210,9 @@ def bw_probe(src, dst=None, sink=None, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(_lib.rose_bw_probe(src.data_ptr(), dst.data_ptr() if dst is not None else None, nbytes,
                               sink.data_ptr() if sink is not None else None, _stream(stream)), "bw_probe")
+
+
+def bw_probe_mixed(src_a, src_b, dst, write_bytes_per_chunk, sink, stream=None):
+    nbytes = src_a.numel() * src_a.element_size()
+    _check(_lib.rose_bw_probe_mixed(src_a.data_ptr(), src_b.data_ptr(), dst.data_ptr(), nbytes,
+                                    write_bytes_per_chunk, sink.data_ptr(), _stream(stream)), "bw_probe_mixed")

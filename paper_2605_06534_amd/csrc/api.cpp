@@ -155,3 +155,15 @@ extern "C" rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, u
     if (!aligned(src, 16) || !aligned(dst, 16) || !aligned(sink, 8)) return ROSE_ERR_ALIGN;
     return rose::launch_bw_probe(src, dst, bytes, sink, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
 }
+
+extern "C" rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
+                                           size_t write_bytes_per_chunk, uint64_t *sink, void *stream) {
+    if (!src_a || !src_b || !dst || !sink) return ROSE_ERR_ARG;
+    if ((read_bytes % ROSE_PROBE_CHUNK) || (write_bytes_per_chunk & 15u) || write_bytes_per_chunk > ROSE_PROBE_CHUNK)
+        return ROSE_ERR_ARG;
+    if (!aligned(src_a, 16) || !aligned(src_b, 16) || !aligned(dst, 16) || !aligned(sink, 8)) return ROSE_ERR_ALIGN;
+    return rose::launch_bw_probe_mixed(src_a, src_b, dst, read_bytes / ROSE_PROBE_CHUNK,
+                                       (uint32_t)(write_bytes_per_chunk / 16), sink, stream) == 0
+               ? ROSE_OK
+               : ROSE_ERR_HIP;
+}

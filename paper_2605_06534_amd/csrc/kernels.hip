@@ -1375,6 +1375,29 @@ __global__ __launch_bounds__(256) void bw_read_kernel(const uint4 *src, size_t n
     if (acc == 0x9E3779B9u) atomicAdd(sink, 1ull);
 }
 
+// Mixed probe: the traffic of an encode launch without any of its work.  Reads two streams in
+// 16 KB chunks (non-temporal, like encode) and writes w16 16-byte vectors per chunk, contiguous
+// across chunks, to a third.
+__global__ __launch_bounds__(256) void bw_mix_kernel(const uint4 *a, const uint4 *b, uint4 *dst, size_t n_chunks,
+                                                     uint32_t w16, u64 *sink) {
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        uint4 va[4], vb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            va[j] = gload16_stream(a + c * 1024 + j * kBwThreads + threadIdx.x);
+            vb[j] = gload16_stream(b + c * 1024 + j * kBwThreads + threadIdx.x);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = xor4(acc, xor4(va[j], vb[j]));
+        for (uint32_t k = threadIdx.x; k < w16; k += kBwThreads) {
+            u32x4 w = {acc.x, acc.y, acc.z, acc.w};
+            __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(dst + c * (size_t)w16 + k)));
+        }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) atomicAdd(sink, 1ull);
+}
+
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
@@ -1484,6 +1507,17 @@ int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, vo
     else
         hipLaunchKernelGGL(bw_read_kernel, dim3(blocks), dim3(kBwThreads), 0, st,
                            static_cast<const uint4 *>(src), n16, reinterpret_cast<u64 *>(sink));
+    return (int)hipGetLastError();
+}
+
+int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, uint64_t *sink,
+                          void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_chunks == 0) return 0;
+    int blocks = n_chunks > 256 * 32 ? 256 * 32 : (int)n_chunks;
+    hipLaunchKernelGGL(bw_mix_kernel, dim3(blocks), dim3(kBwThreads), 0, st, static_cast<const uint4 *>(a),
+                       static_cast<const uint4 *>(b), static_cast<uint4 *>(dst), n_chunks, w16,
+                       reinterpret_cast<u64 *>(sink));
     return (int)hipGetLastError();
 }
 

@@ -118,6 +118,8 @@ int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_num
                  void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
 int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
+int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, uint64_t *sink,
+                          void *stream);
 
 }  // namespace rose
 

@@ -216,3 +216,35 @@ def test_argument_errors_on_device_calls():
         R.delta_apply(c.plan, 2, c.buckets[0], c.old_tab)
     assert e.value.status == 1
     torch.cuda.synchronize()
+
+
+def test_bandwidth_probes_move_what_they_say():
+    """The probes are measurement aids; what can be checked: the copy probe copies, the mixed probe
+    writes exactly the stated bytes per chunk and nothing beyond, bad sizes are refused."""
+    print("case: bandwidth probes", flush=True)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    a = torch.randint(0, 255, (4 * 16384,), dtype=torch.uint8, generator=g).cuda()
+    b = torch.randint(0, 255, (4 * 16384,), dtype=torch.uint8, generator=g).cuda()
+    out = torch.zeros_like(a)
+    sink = torch.zeros(1, dtype=torch.int64, device="cuda")
+    R.bw_probe(a, out, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(a, out)
+    per_chunk = 48
+    dst = torch.full((4 * per_chunk + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    R.bw_probe_mixed(a, b, dst, per_chunk, sink)
+    torch.cuda.synchronize()
+    assert bool((dst[4 * per_chunk:] == 0x5A).all()), "the mixed probe wrote past its output"
+    # every 16-byte vector of a chunk's output is some thread's running XOR of what it has read so
+    # far; thread 0 of the workgroup that handles chunk c (one chunk per workgroup here) has read
+    # the vectors 0, 256, 512, 768 of both inputs
+    av, bv = a.view(-1, 16).cpu().numpy(), b.view(-1, 16).cpu().numpy()
+    for c in range(4):
+        want = np.zeros(16, dtype=np.uint8)
+        for j in range(4):
+            want ^= av[c * 1024 + j * 256] ^ bv[c * 1024 + j * 256]
+        assert np.array_equal(dst[c * per_chunk:c * per_chunk + 16].cpu().numpy(), want), c
+    with pytest.raises(R.RoseError):
+        R.bw_probe_mixed(a[:1000], b[:1000], dst, per_chunk, sink)
+    with pytest.raises(R.RoseError):
+        R.bw_probe_mixed(a, b, dst, 50, sink)
