@@ -26,7 +26,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="decoder7b_tp4",
-                    choices=["matrix4096_tp1", "decoder7b_tp4", "flat1g_tp1", "decoder32b_tp8", "decoder32b_tp8_f32"])
+                    choices=["matrix4096_tp1", "decoder7b_tp4", "flat1g_tp1", "decoder32b_tp8", "decoder32b_tp8_f32",
+                             "decoder8b_tp1", "decoder8b_tp4"])
     ap.add_argument("--density", type=float, default=None, help="change density p (default: the workload's)")
     ap.add_argument("--layers", type=int, default=None, help="fewer decoder layers (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
@@ -48,6 +49,8 @@ def workload(args):
         return models.flat(1 << 30), 1, "bernoulli", 0.01
     if w == "decoder32b_tp8":
         return models.decoder_32b(args.layers or 64), 8, "bernoulli", 0.02
+    if w in ("decoder8b_tp1", "decoder8b_tp4"):
+        return models.decoder_8b(args.layers or 36), 1 if w.endswith("tp1") else 4, "bernoulli", 0.02
     return models.decoder_32b(args.layers or 64), 8, "clustered_f32", None
 
 

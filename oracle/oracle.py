@@ -53,6 +53,8 @@ def _load():
         lib.orc_shard_map.argtypes = [i32, i64, i64, i32, vp, i32, i64, i64, vp, vp, vp]
         lib.orc_encode_tensor.restype = i32
         lib.orc_encode_tensor.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, vp, vp, vp]
+        lib.orc_encode_tensor_src.restype = i32
+        lib.orc_encode_tensor_src.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, i32, i32, i32, vp, vp, vp]
         lib.orc_apply.restype = i32
         lib.orc_apply.argtypes = [vp, vp, i64, vp, i64]
         lib.orc_dense_shard.restype = i32
@@ -128,6 +130,38 @@ def encode_tensor(old, new, rows, cols, rule, sections, tp):
     rc = lib.orc_encode_tensor(old.ctypes.data, new.ctypes.data, is_f32, rule, rows, cols,
                                sec.size, secp, tp, counts2.ctypes.data, pi, pv)
     _check(rc, "encode_tensor(fill)")
+    assert (counts == counts2).all()
+    return list(zip(idx, val))
+
+
+def encode_tensor_src(old_slice, new_slice, rows, cols, rule, sections, tp_dst, tp_src, src_rank,
+                      sends_replicated=True):
+    """Dense-to-sparse of one tensor by the sender that holds shard `src_rank` of `tp_src` of it
+    (rows, cols are the FULL tensor's) -> list over destination shards of (idx int32, val uint16)."""
+    lib = _load()
+    old = np.ascontiguousarray(old_slice).view(np.uint16).ravel()
+    new = np.ascontiguousarray(new_slice).ravel()
+    if new.dtype.itemsize == 4:
+        new, is_f32 = new.view(np.uint32), 1
+    elif new.dtype.itemsize == 2:
+        new, is_f32 = new.view(np.uint16), 0
+    else:
+        raise OracleError("new must hold 16-bit or 32-bit patterns")
+    want = local_numel(rule, rows, cols, tp_src)
+    if old.size != want or new.size != want:
+        raise OracleError("slice sizes do not match the sender's shard")
+    sec, secp = _sections(sections)
+    args = (is_f32, rule, rows, cols, sec.size, secp, tp_dst, tp_src, src_rank, 1 if sends_replicated else 0)
+    counts = np.zeros(tp_dst, dtype=np.int64)
+    _check(lib.orc_encode_tensor_src(old.ctypes.data, new.ctypes.data, *args, counts.ctypes.data, None, None),
+           "encode_tensor_src(count)")
+    idx = [np.empty(int(n), dtype=np.int32) for n in counts]
+    val = [np.empty(int(n), dtype=np.uint16) for n in counts]
+    pi = (ctypes.c_void_p * tp_dst)(*[a.ctypes.data for a in idx])
+    pv = (ctypes.c_void_p * tp_dst)(*[a.ctypes.data for a in val])
+    counts2 = np.zeros(tp_dst, dtype=np.int64)
+    _check(lib.orc_encode_tensor_src(old.ctypes.data, new.ctypes.data, *args, counts2.ctypes.data, pi, pv),
+           "encode_tensor_src(fill)")
     assert (counts == counts2).all()
     return list(zip(idx, val))
 

@@ -189,6 +189,59 @@ int orc_encode_tensor(const uint16_t *old_bits, const void *new_data, int new_is
 }
 
 /*
+ * The same for a sender that holds only ITS OWN slice of the tensor (Sec. 4.2: the sharded
+ * dimension gives per-rank slice ranges on BOTH sides; train and serve degrees may differ).
+ * The sender is rank s of S under the same rule: old_slice / new_slice are shard s of the full
+ * tensors (orc_dense_shard with degree S).  A replicated tensor is held by every sender; it is
+ * sent by one of them only, which the caller names with sends_replicated != 0.
+ *
+ * Written over the FULL tensor's coordinates: element (r,c) is emitted by the sender whose slice
+ * holds it (shard map with degree S gives the sender and the index inside its slice) to the
+ * destination the shard map with degree D gives.  Entries come out in ascending (r,c).
+ */
+int orc_encode_tensor_src(const uint16_t *old_slice, const void *new_slice, int new_is_f32,
+                          int rule, int64_t R, int64_t C, int n_sec, const int64_t *sec,
+                          int D, int S, int s, int sends_replicated,
+                          int64_t *counts, int32_t *const *idx, uint16_t *const *val)
+{
+    int rc = check_shape(rule, R, C, n_sec, sec, D);
+    if (rc) return rc;
+    rc = check_shape(rule, R, C, n_sec, sec, S);
+    if (rc) return rc;
+    if (s < 0 || s >= S) return ORC_RANGE;
+    if (orc_local_numel(rule, R, C, D) > (int64_t)INT32_MAX) return ORC_RANGE;
+    for (int d = 0; d < D; ++d) counts[d] = 0;
+    if (rule == ORC_REPLICATED && !sends_replicated) return ORC_OK;
+
+    const uint16_t *new16 = (const uint16_t *)new_slice;
+    const uint32_t *new32 = (const uint32_t *)new_slice;
+
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t c = 0; c < C; ++c) {
+            int s_first, n_src; int64_t sl;
+            rc = orc_shard_map(rule, R, C, n_sec, sec, S, r, c, &s_first, &n_src, &sl);
+            if (rc) return rc;
+            if (s < s_first || s >= s_first + n_src) continue;      /* another sender's element */
+            uint16_t nb = new_is_f32 ? orc_rne_bf16(new32[sl]) : new16[sl];
+            if (nb == old_slice[sl]) continue;
+            int d_first, n_dest; int64_t local;
+            rc = orc_shard_map(rule, R, C, n_sec, sec, D, r, c, &d_first, &n_dest, &local);
+            if (rc) return rc;
+            for (int d = d_first; d < d_first + n_dest; ++d) {
+                int64_t k = counts[d];
+                if (idx) {
+                    if (k > 0 && (int64_t)idx[d][k - 1] >= local) return ORC_ORDER;
+                    idx[d][k] = (int32_t)local;
+                    val[d][k] = nb;
+                }
+                counts[d] = k + 1;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/*
  * Sparse-to-dense (App. F "S2D"): put each entry's value at its local index
  * of the receiver's resident copy.  Nothing else is touched.
  */

@@ -151,6 +151,16 @@ def test_decoder32b_tp8_p02():
     run_and_check(ts, 8, "bernoulli", 0, sample, density=0.02, p=0.02)
 
 
+@pytest.mark.parametrize("tp", [1, 4])
+def test_decoder8b_shapes(tp):
+    """8B-style GQA decoder (the paper's smaller model), at the rollout side's TP=1 and the training
+    side's TP=4; Bernoulli(0.02)."""
+    print("case: decoder8b tp=%d p=0.02 seed=1" % tp, flush=True)
+    ts = models.decoder_8b()
+    sample = [0, 1, 2, 3, 5, 6, len(ts) - 2, len(ts) - 1]
+    run_and_check(ts, tp, "bernoulli", 1, sample, density=0.02, p=0.02)
+
+
 def test_decoder32b_tp8_fp32_master_clustered():
     """fp32-master input with per-row Beta(0.5, 20) change rates, 32B shapes at 8 of 64 layers (the
     full set with an fp32 copy does not leave room for the receiver's shards on one GPU)."""

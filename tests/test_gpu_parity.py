@@ -218,6 +218,19 @@ def test_argument_errors_on_device_calls():
     torch.cuda.synchronize()
 
 
+def test_pipeline_stages_encode_independently():
+    """PP-aware use (Sec. 4.2 supports TP and PP): each pipeline stage plans, encodes and applies
+    only the tensors it holds; together the stages cover the model exactly once."""
+    print("case: pipeline stages pp=2 tp=2", flush=True)
+    ts = models.decoder(4, 256, 8, 4, 32, 704, 1024, fused=True)
+    seen = []
+    for stage in range(2):
+        sub = models.pp_stage(ts, 4, 2, stage)
+        seen += [i for i, _ in sub]
+        full_parity(bern_case([t for _, t in sub], 2, 0.05, seed=20 + stage), check_dense=False)
+    assert sorted(seen) == list(range(len(ts)))
+
+
 def test_bandwidth_probes_move_what_they_say():
     """The probes are measurement aids; what can be checked: the copy probe copies, the mixed probe
     writes exactly the stated bytes per chunk and nothing beyond, bad sizes are refused."""

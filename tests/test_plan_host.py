@@ -103,3 +103,14 @@ def test_empty_tensor_gets_a_tile():
     p = R.shard_plan([dict(rows=0, cols=8, rule=R.SPLIT_ROWS, sections=None),
                       dict(rows=4, cols=8, rule=R.SPLIT_ROWS, sections=None)], 2)
     assert p.n_tiles() == 4 and p.local_numel(0, 1) == 0
+
+
+def test_pp_stage_helper_partitions_the_model():
+    from workloads import models
+    ts = models.decoder_8b(layers=8)
+    for pp in (1, 2, 4, 8):
+        got = [i for st in range(pp) for i, _ in models.pp_stage(ts, 8, pp, st)]
+        assert got == list(range(len(ts)))
+    assert models.pp_stage(ts, 8, 4, 0)[0][1]["name"] == "embed"
+    assert models.pp_stage(ts, 8, 4, 3)[-1][1]["name"] == "lm_head"
+    assert models.numel(models.decoder_8b()) == 8190726144

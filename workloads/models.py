@@ -65,5 +65,32 @@ def decoder_32b(layers=64):
     return decoder(layers, 5120, 40, 8, 128, 27648, 152064, True)
 
 
+def decoder_8b(layers=36):
+    """8B-style GQA decoder (hidden 4096, 32 query / 8 KV heads of 128, SwiGLU 12288, vocab 151936),
+    the paper's smaller model (Sec. 5: TP=4 for training, TP=1 for rollout)."""
+    return decoder(layers, 4096, 32, 8, 128, 12288, 151936, True)
+
+
+def pp_stage(tensors, layers, pp, stage):
+    """The tensors a pipeline stage holds (Sec. 4.2: the transfer engine supports TP and PP): layers
+    are dealt to the pp stages in equal consecutive groups, the embedding goes with the first stage,
+    final norm and lm_head with the last.  Returns (ordinal in `tensors`, descriptor) pairs, in order."""
+    if layers % pp:
+        raise ValueError("layers must divide evenly over the pipeline stages")
+    per = layers // pp
+    out = []
+    for i, t in enumerate(tensors):
+        n = t["name"]
+        if n == "embed":
+            s = 0
+        elif n in ("final_norm", "lm_head"):
+            s = pp - 1
+        else:
+            s = int(n[1:n.index(".")]) // per
+        if s == stage:
+            out.append((i, t))
+    return out
+
+
 def numel(tensors):
     return sum(t["rows"] * t["cols"] for t in tensors)
