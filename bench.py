@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--density", type=float, default=None, help="change density p (default: the workload's)")
     ap.add_argument("--layers", type=int, default=None, help="fewer decoder layers (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--tp-src", type=int, default=1,
+                    help="sender-side sharding: time the sender that holds shard --src-rank of this many")
+    ap.add_argument("--src-rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=float, default=2.0e9)
     ap.add_argument("--traffic-bytes", type=float, default=None,
@@ -81,16 +84,32 @@ def main():
         olds.append(o)
         news.append(n)
     new_dtype = R.FP32_RNE if recipe == "clustered_f32" else R.BF16
-    plan = R.shard_plan(tensors, tp)
+    if args.tp_src > 1:
+        # the sender's slices of W_{t-1} and W_t, cut with the library's own dense path
+        if new_dtype != R.BF16:
+            print("bench.py: --tp-src is for bf16 workloads", file=sys.stderr)
+            sys.exit(2)
+        cut = R.shard_plan(tensors, args.tp_src)
+        full_old, full_new = R.ptr_table(olds), R.ptr_table(news)
+        so = [torch.empty(cut.local_numel(t, args.src_rank), dtype=torch.bfloat16, device=dev) for t in range(len(tensors))]
+        sn = [torch.empty_like(x) for x in so]
+        R.dense_copy(cut, args.src_rank, full_old, R.BF16, R.ptr_table(so))
+        R.dense_copy(cut, args.src_rank, full_new, R.BF16, R.ptr_table(sn))
+        torch.cuda.synchronize()
+        olds, news = so, sn
+        del cut, full_old, full_new
+        torch.cuda.empty_cache()
+        n_elems = sum(x.numel() for x in olds)
+    plan = R.shard_plan(tensors, tp, args.tp_src, args.src_rank)
     old_tab, new_tab = R.ptr_table(olds), R.ptr_table(news)
     ws = R.workspace(plan)
     frac = 0.06 if p is None else min(1.0, 1.3 * p + 0.002)
     buckets = [R.Bucket(int(plan.bucket_capacity(d) * frac) + 4096, len(tensors)) for d in range(tp)]
     shards, shard_tabs = [], []
     for d in range(tp):
-        loc = [torch.empty(plan.local_numel(t, d), dtype=torch.bfloat16, device=dev) for t in range(len(tensors))]
+        loc = [torch.zeros(plan.local_numel(t, d), dtype=torch.bfloat16, device=dev) for t in range(len(tensors))]
         tab = R.ptr_table(loc)
-        R.dense_copy(plan, d, old_tab, R.BF16, tab)        # receiver starts from W_{t-1}
+        R.dense_copy(plan, d, old_tab, R.BF16, tab)        # receiver starts from W_{t-1} (the part this sender covers)
         shards.append(loc)
         shard_tabs.append(tab)
     torch.cuda.synchronize()
@@ -113,7 +132,7 @@ def main():
     nnz_total = sum(nnz)
 
     # the receiver now holds W_t: check one shard tensor per rule class against a dense copy
-    chk = [torch.empty_like(x) for x in shards[tp - 1]]
+    chk = [x.clone() for x in shards[tp - 1]]
     R.dense_copy(plan, tp - 1, new_tab, new_dtype, R.ptr_table(chk))
     torch.cuda.synchronize()
     for a, b in zip(shards[tp - 1], chk):
@@ -212,6 +231,7 @@ def main():
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": args.workload, "elements": n_elems, "tensors": len(tensors), "tp": tp,
                    "recipe": recipe, "density": p, "nnz": nnz_total, "seed": args.seed,
+                   "tp_src": args.tp_src, "src_rank": args.src_rank,
                    "new_dtype": "fp32->bf16 RNE" if new_dtype == R.FP32_RNE else "bf16"},
         "roofline": {"bound": "hbm", "kernel": "encode_kernel",
                      "achieved": round(enc_bytes / 1e9 / (t_enc / 1e3), 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -231,7 +251,7 @@ def main():
                    "bw_probe": probe, "tiles": plan.n_tiles()},
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.tp_src == 1:
         out["cpu_baseline"] = cpu_baseline(tensors, tp, olds, news, args.cpu_sample_elems, in_bytes_per_elem)
     print(json.dumps(out), flush=True)
 

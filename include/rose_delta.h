@@ -99,6 +99,21 @@ typedef struct {
  */
 rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
                                    rose_plan **out);
+/*
+ * The same for a sender that holds only its own slice of every tensor (Sec. 4.2: per-rank slice
+ * ranges on both sides; training and serving may use different degrees): the sender is rank
+ * src_rank of tp_src under the SAME rule per tensor, and old / new pointers given to
+ * rose_delta_encode point at its slices (rose_plan_src_numel elements each, laid out like a
+ * destination shard of degree tp_src).  Each element goes to the destination shard that holds it,
+ * at that shard's local index; a destination is only reached where the two slice ranges overlap.
+ * A replicated tensor is held by every sender and sent by exactly one: sender (ordinal mod
+ * tp_src); the others' pointers for it are not read.  The tp_src senders' buckets for one
+ * destination are disjoint and may be applied in any order.  tp_src = 1, src_rank = 0 is
+ * rose_shard_plan_create.  rose_dense_copy with such a plan copies the part of the destination
+ * shard that the sender holds.  Errors as above; both degrees must divide the split dimensions.
+ */
+rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
+                                       int32_t tp_src, int32_t src_rank, rose_plan **out);
 void rose_shard_plan_destroy(rose_plan *plan);
 
 /* Host queries on a plan (no GPU needed). */
@@ -108,10 +123,13 @@ int32_t rose_plan_tp(const rose_plan *plan);
 rose_status rose_plan_tensor_base(const rose_plan *plan, int32_t t, int64_t *global_base);
 /* elements of shard d's local copy of tensor t */
 rose_status rose_plan_local_numel(const rose_plan *plan, int32_t t, int32_t d, int64_t *numel);
-/* flat element g of tensor t lives on shards d_first .. d_first + n_dest - 1 at local index *local */
+/* elements of the sender's slice of tensor t (the full tensor unless the plan has tp_src > 1) */
+rose_status rose_plan_src_numel(const rose_plan *plan, int32_t t, int64_t *numel);
+/* flat element g of the sender's slice of tensor t goes to shards d_first .. d_first + n_dest - 1 at
+ * local index *local (n_dest = 0: a replicated tensor that another sender sends) */
 rose_status rose_plan_map_index(const rose_plan *plan, int32_t t, int64_t g, int32_t *d_first,
                                 int32_t *n_dest, int32_t *local);
-/* worst-case number of entries of bucket d (every element changed) */
+/* worst-case number of entries this sender produces for bucket d (every element changed) */
 rose_status rose_plan_bucket_capacity(const rose_plan *plan, int32_t d, int64_t *max_entries);
 /* bytes of device scratch that rose_delta_encode needs (256-byte aligned buffer) */
 rose_status rose_plan_workspace_bytes(const rose_plan *plan, size_t *bytes);

@@ -37,11 +37,13 @@ _vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
 _P = ctypes.POINTER
 _SIGS = {
     "rose_shard_plan_create": (_i32, [_P(TensorDesc), _i32, _i32, _P(_vp)]),
+    "rose_shard_plan_create_src": (_i32, [_P(TensorDesc), _i32, _i32, _i32, _i32, _P(_vp)]),
     "rose_shard_plan_destroy": (None, [_vp]),
     "rose_plan_n_tensors": (_i32, [_vp]),
     "rose_plan_tp": (_i32, [_vp]),
     "rose_plan_tensor_base": (_i32, [_vp, _i32, _P(_i64)]),
     "rose_plan_local_numel": (_i32, [_vp, _i32, _i32, _P(_i64)]),
+    "rose_plan_src_numel": (_i32, [_vp, _i32, _P(_i64)]),
     "rose_plan_map_index": (_i32, [_vp, _i32, _i64, _P(_i32), _P(_i32), _P(_i32)]),
     "rose_plan_bucket_capacity": (_i32, [_vp, _i32, _P(_i64)]),
     "rose_plan_workspace_bytes": (_i32, [_vp, _P(ctypes.c_size_t)]),
@@ -111,6 +113,11 @@ class Plan:
         _check(_lib.rose_plan_tensor_base(self._h, t, ctypes.byref(v)), "plan_tensor_base")
         return v.value
 
+    def src_numel(self, t):
+        v = _i64()
+        _check(_lib.rose_plan_src_numel(self._h, t, ctypes.byref(v)), "plan_src_numel")
+        return v.value
+
     def local_numel(self, t, d):
         v = _i64()
         _check(_lib.rose_plan_local_numel(self._h, t, d, ctypes.byref(v)), "plan_local_numel")
@@ -138,8 +145,9 @@ class Plan:
         return v.value
 
 
-def shard_plan(tensors, tp):
-    """tensors: list of dicts with rows, cols, rule and (fused rows) sections."""
+def shard_plan(tensors, tp, tp_src=1, src_rank=0):
+    """tensors: list of dicts with rows, cols, rule and (fused rows) sections.  With tp_src > 1 the
+    plan is for the sender that holds shard src_rank of tp_src of every tensor."""
     arr = (TensorDesc * max(len(tensors), 1))()
     for i, t in enumerate(tensors):
         arr[i].rows, arr[i].cols, arr[i].rule = t["rows"], t["cols"], t["rule"]
@@ -150,7 +158,10 @@ def shard_plan(tensors, tp):
         for j, s in enumerate(sec):
             arr[i].section_rows[j] = s
     h = _vp()
-    _check(_lib.rose_shard_plan_create(arr, len(tensors), tp, ctypes.byref(h)), "shard_plan")
+    if tp_src == 1 and src_rank == 0:
+        _check(_lib.rose_shard_plan_create(arr, len(tensors), tp, ctypes.byref(h)), "shard_plan")
+    else:
+        _check(_lib.rose_shard_plan_create_src(arr, len(tensors), tp, tp_src, src_rank, ctypes.byref(h)), "shard_plan")
     return Plan(h, list(tensors))
 
 

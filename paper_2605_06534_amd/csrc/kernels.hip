@@ -125,6 +125,15 @@ __device__ __forceinline__ int64_t src_index(const Piece &pc, uint32_t k, bool u
     return pc.src_off + k;
 }
 
+// shard-local index of element k of the piece
+__device__ __forceinline__ uint32_t dst_index(const Piece &pc, uint32_t k, bool use_magic) {
+    if (pc.flags & kPieceDstStrided) {
+        uint32_t q = use_magic ? (__umulhi(k, pc.magic) >> pc.shift) : (k / (uint32_t)pc.run);
+        return (uint32_t)pc.local_base + q * (uint32_t)pc.lstride + (k - q * (uint32_t)pc.run);
+    }
+    return (uint32_t)pc.local_base + k;
+}
+
 // Tile loaders.  A lane's vector j holds the eight 16-bit patterns at piece-relative local indices
 // k .. k+7 with k = k_wave + (j * 64 + lane) * 8.
 //
@@ -420,12 +429,13 @@ struct TileCtx {
     uint32_t k_tile;
     uint32_t limit;     // see load_raw
     uint32_t vec;       // 128-bit loads are legal for this tile
-    uint32_t pad;       // no padding bytes: the struct is copied between registers only
+    int32_t piece;      // index of pc in the piece table
 };
 
 __device__ __forceinline__ TileCtx tile_ctx(const EncodeArgs &a, int32_t tile) {
     TileCtx c;
-    c.pc = load_piece(a.pieces + cload32(a.tile_piece + tile));
+    c.piece = cload32(a.tile_piece + tile);
+    c.pc = load_piece(a.pieces + c.piece);
     c.old_base = reinterpret_cast<const uint16_t *>(cload64(a.old_ptrs + c.pc.tensor));
     c.new_base = reinterpret_cast<const void *>(cload64(a.new_ptrs + c.pc.tensor));
     c.k_tile = (uint32_t)(tile - c.pc.first_tile) * (uint32_t)kTile;
@@ -433,14 +443,15 @@ __device__ __forceinline__ TileCtx tile_ctx(const EncodeArgs &a, int32_t tile) {
     // uniform choice: aligned piece and aligned tensors -> 128-bit loads
     c.vec = ((c.pc.flags & kPieceVec) && ((((uintptr_t)c.old_base) | ((uintptr_t)c.new_base)) & 15u) == 0 &&
              c.k_tile + (uint32_t)kVec <= (uint32_t)c.pc.len) ? 1u : 0u;
-    c.pad = 0;
     return c;
 }
 
 // What a worker keeps of a tile while it handles it (uniform, a few scalars: the full context is
 // only needed to issue the loads and in rare paths, which build it again).
 struct TileMeta {
-    uint32_t out_base;  // local index of the tile's first element
+    uint32_t out_base;  // local index of the tile's first element (piece with contiguous local indices),
+                        // else the tile's first element number k inside its piece
+    int32_t piece;      // -1, or the piece whose table entry maps element numbers to local indices
     int32_t shard;
     int32_t seg;        // tensor whose segment starts with this tile, else -1
     uint32_t limit;     // see load_raw
@@ -449,7 +460,9 @@ struct TileMeta {
 };
 __device__ __forceinline__ TileMeta tile_meta(const TileCtx &c, int32_t tile) {
     TileMeta m;
-    m.out_base = (uint32_t)c.pc.local_base + c.k_tile;
+    const bool dst_strided = (c.pc.flags & kPieceDstStrided) != 0;
+    m.out_base = dst_strided ? c.k_tile : (uint32_t)c.pc.local_base + c.k_tile;
+    m.piece = dst_strided ? c.piece : -1;
     m.shard = c.pc.shard;
     m.seg = ((c.pc.flags & kPieceFirst) && tile == c.pc.first_tile) ? c.pc.tensor : -1;
     m.limit = c.limit;
@@ -578,7 +591,8 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     __shared__ int32_t s_nready[2];
     __shared__ uint32_t s_q_count[kQueue];
     __shared__ uint32_t s_q_off[kQueue];
-    __shared__ uint32_t s_q_base[kQueue];   // local index of the tile's first element
+    __shared__ uint32_t s_q_base[kQueue];   // see TileMeta::out_base
+    __shared__ int32_t s_q_piece[kQueue];   // see TileMeta::piece
     __shared__ int32_t s_q_shard[kQueue];
     __shared__ int32_t s_q_seg[kQueue];     // tensor whose segment starts with this tile, else -1
     __shared__ int32_t s_q_last[kQueue];    // 1 if the tile is the last of its chain
@@ -642,15 +656,31 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                     if (seg >= 0) b.seg_off[seg] = (int64_t)excl;
                     if (last) b.seg_off[a.n_tensors] = (int64_t)(excl + cnt);
                 }
+                const int32_t piece = __builtin_amdgcn_readfirstlane(s_q_piece[slot]);
+                // local index of the element at offset o of the tile
+                uint32_t l_base = base, l_run = 0, l_magic = 0, l_shift = 0, l_stride = 0;
+                if (piece >= 0) {                      // the piece's local indices come in strided runs
+                    const Piece pc = load_piece(a.pieces + piece);
+                    l_base = (uint32_t)pc.local_base;
+                    l_run = (uint32_t)pc.run;
+                    l_magic = pc.magic;
+                    l_shift = pc.shift;
+                    l_stride = (uint32_t)pc.lstride;
+                }
                 for (uint32_t k = threadIdx.x; k < cnt; k += kThreads) {
                     const u64 pos = excl + k;
                     if (pos < (u64)b.capacity) {
                         const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
+                        uint32_t local = base + (entry >> 16);
+                        if (piece >= 0) {              // base is the tile's first element number here
+                            const uint32_t q = __umulhi(local, l_magic) >> l_shift;
+                            local = l_base + q * l_stride + (local - q * l_run);
+                        }
 #if ROSE_NT_STORES
-                        __builtin_nontemporal_store((int32_t)(base + (entry >> 16)), b.idx + pos);
+                        __builtin_nontemporal_store((int32_t)local, b.idx + pos);
                         __builtin_nontemporal_store((uint16_t)entry, b.val + pos);
 #else
-                        b.idx[pos] = (int32_t)(base + (entry >> 16));
+                        b.idx[pos] = (int32_t)local;
                         b.val[pos] = (uint16_t)entry;
 #endif
                     }
@@ -978,6 +1008,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 s_q_count[slot] = tile_total;
                 s_q_off[slot] = ring_head;
                 s_q_base[slot] = cur.out_base;
+                s_q_piece[slot] = cur.piece;
                 s_q_shard[slot] = cur.shard;
                 s_q_seg[slot] = seg;
                 s_q_last[slot] = tile == chain_last;
@@ -1016,6 +1047,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             __syncthreads();
             const u64 tile_excl = s_direct_excl;
             const BucketDev b = a.bucket[cur.shard];
+            const Piece big_pc = load_piece(a.pieces + (cur.piece >= 0 ? cur.piece : 0));
             if (s_ok && !(ROSE_DIAG & 2)) {
                 if (threadIdx.x == 0) {
                     if (seg >= 0) b.seg_off[seg] = (int64_t)tile_excl;
@@ -1026,12 +1058,14 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 for (int j = 0; j < kIters; ++j) {
                     uint32_t m = mask[j];
                     u64 pos = wave_base + rank[j];
+                    // cur.out_base + offset is the local index, or (strided local indices) the
+                    // element number that the piece maps to one
                     const uint32_t local0 = cur.out_base + t_off + (uint32_t)(j * 64) * kVec;
                     while (m) {
                         const uint32_t e = __ffs(m) - 1;
                         m &= m - 1;
                         if (pos < (u64)b.capacity) {
-                            b.idx[pos] = (int32_t)(local0 + e);
+                            b.idx[pos] = (int32_t)(cur.piece >= 0 ? dst_index(big_pc, local0 + e, false) : local0 + e);
                             b.val[pos] = (uint16_t)pick16(nv[j], e);
                         }
                         ++pos;
@@ -1320,7 +1354,7 @@ __global__ __launch_bounds__(kThreads) void dense_copy_kernel(CopyArgs a) {
         load_tile_fast<NEW_F32>(new_base, pc, k_wave, lane, nv);
 #pragma unroll
         for (int j = 0; j < kIters; ++j)
-            gstore16(dst + (uint32_t)pc.local_base + k_wave + (uint32_t)(j * 64 + lane) * kVec, nv[j]);
+            gstore16(dst + dst_index(pc, k_wave + (uint32_t)(j * 64 + lane) * kVec, true), nv[j]);
     } else {
 #pragma unroll 1
         for (int j = 0; j < kIters; ++j) {
@@ -1328,7 +1362,7 @@ __global__ __launch_bounds__(kThreads) void dense_copy_kernel(CopyArgs a) {
             uint4 n = load_vec_general<NEW_F32>(new_base, pc, k);
 #pragma unroll
             for (uint32_t i = 0; i < (uint32_t)kVec; ++i)
-                if (k + i < (uint32_t)pc.len) dst[(uint32_t)pc.local_base + k + i] = (uint16_t)pick16(n, i);
+                if (k + i < (uint32_t)pc.len) dst[dst_index(pc, k + i, false)] = (uint16_t)pick16(n, i);
         }
     }
 }

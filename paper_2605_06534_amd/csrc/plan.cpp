@@ -70,11 +70,20 @@ static int64_t local_numel(const rose_tensor_desc &t, int32_t tp) {
     return t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : tp);
 }
 
-// pieces of segment (t, d), in ascending local index
-static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int32_t tp,
+// does sender `src_rank` of `tp_src` send tensor ordinal ti?  A replicated tensor is held by every
+// sender and sent by exactly one (dealt round robin); every other tensor is sent by all, each its slice.
+static bool sends(const rose_tensor_desc &t, int32_t ti, int32_t tp_src, int32_t src_rank) {
+    return t.rule != ROSE_REPLICATED || ti % tp_src == src_rank;
+}
+
+// pieces of segment (t, d) that sender s of S holds, in ascending local index
+static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int32_t D, int32_t S, int32_t s,
                            std::vector<Piece> &out) {
     size_t first = out.size();
-    auto add = [&](int64_t src_off, int64_t local_base, int64_t len, int64_t run, int64_t stride) {
+    // a part of `len` elements in runs of `run`: the sender's slice advances by src_stride per run,
+    // the destination's local index by lstride per run (both equal to run when contiguous)
+    auto add = [&](int64_t src_off, int64_t src_stride, int64_t local_base, int64_t lstride, int64_t run,
+                   int64_t len) {
         if (len <= 0) return;
         Piece p;
         std::memset(&p, 0, sizeof p);
@@ -83,34 +92,54 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
         p.shard = d;
         p.local_base = (int32_t)local_base;
         p.len = (int32_t)len;
-        bool strided = run < len && stride != run;
+        const bool src_strided = run < len && src_stride != run;
+        const bool dst_strided = run < len && lstride != run;
+        const bool strided = src_strided || dst_strided;
         p.run = (int32_t)(strided ? run : len);
-        p.stride = strided ? stride : len;
-        if (strided) {
-            p.flags |= rose::kPieceStrided;
-            if (run >= 2) rose::make_magic((uint32_t)run, &p.magic, &p.shift);
-        }
+        p.stride = src_strided ? src_stride : p.run;
+        p.lstride = (int32_t)(dst_strided ? lstride : p.run);
+        if (src_strided) p.flags |= rose::kPieceStrided;
+        if (dst_strided) p.flags |= rose::kPieceDstStrided;
+        if (strided && run >= 2) rose::make_magic((uint32_t)run, &p.magic, &p.shift);
         bool vec = (src_off % rose::kVec == 0) && (local_base % rose::kVec == 0) &&
-                   (!strided || (run % rose::kVec == 0 && stride % rose::kVec == 0));
+                   (!strided || run % rose::kVec == 0) && (!src_strided || src_stride % rose::kVec == 0) &&
+                   (!dst_strided || lstride % rose::kVec == 0);
         if (strided && vec && !rose::magic_ok((uint32_t)run, p.magic, p.shift, (uint32_t)len)) vec = false;
         if (vec) p.flags |= rose::kPieceVec;
         out.push_back(p);
     };
+    // rows (or columns) [lo, hi) that both the sender's block and the destination's block hold
+    auto overlap = [](int64_t a0, int64_t a1, int64_t b0, int64_t b1, int64_t *lo, int64_t *hi) {
+        *lo = a0 > b0 ? a0 : b0;
+        *hi = a1 < b1 ? a1 : b1;
+        return *hi > *lo;
+    };
     const int64_t R = t.rows, C = t.cols;
-    switch (t.rule) {
-    case ROSE_REPLICATED: add(0, 0, R * C, R * C, R * C); break;
-    case ROSE_SPLIT_ROWS: add(d * (R / tp) * C, 0, (R / tp) * C, (R / tp) * C, 0); break;
-    case ROSE_SPLIT_COLS: add(d * (C / tp), 0, R * (C / tp), C / tp, C); break;
-    case ROSE_FUSED_ROWS: {
-        int64_t sec_row = 0, loc_row = 0;
-        for (int j = 0; j < t.n_sections; ++j) {
-            int64_t per = t.section_rows[j] / tp;
-            add((sec_row + d * per) * C, loc_row * C, per * C, per * C, 0);
-            sec_row += t.section_rows[j];
-            loc_row += per;
+    int64_t lo, hi;
+    if (sends(t, ti, S, s)) {
+        switch (t.rule) {
+        case ROSE_REPLICATED: add(0, R * C, 0, R * C, R * C, R * C); break;
+        case ROSE_SPLIT_ROWS:
+            if (overlap(s * (R / S), (s + 1) * (R / S), d * (R / D), (d + 1) * (R / D), &lo, &hi))
+                add((lo - s * (R / S)) * C, 0, (lo - d * (R / D)) * C, 0, (hi - lo) * C, (hi - lo) * C);
+            break;
+        case ROSE_SPLIT_COLS:
+            if (overlap(s * (C / S), (s + 1) * (C / S), d * (C / D), (d + 1) * (C / D), &lo, &hi))
+                add(lo - s * (C / S), C / S, lo - d * (C / D), C / D, hi - lo, R * (hi - lo));
+            break;
+        case ROSE_FUSED_ROWS: {
+            int64_t src_row = 0, loc_row = 0;     // first row of section j in the sender's slice / the shard
+            for (int j = 0; j < t.n_sections; ++j) {
+                const int64_t per_s = t.section_rows[j] / S, per_d = t.section_rows[j] / D;
+                if (overlap(s * per_s, (s + 1) * per_s, d * per_d, (d + 1) * per_d, &lo, &hi))
+                    add((src_row + lo - s * per_s) * C, 0, (loc_row + lo - d * per_d) * C, 0, (hi - lo) * C,
+                        (hi - lo) * C);
+                src_row += per_s;
+                loc_row += per_d;
+            }
+            break;
         }
-        break;
-    }
+        }
     }
     if (out.size() == first) {   // empty segment: keep one empty piece so the segment has a tile
         Piece p;
@@ -123,20 +152,23 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
     out[first].flags |= rose::kPieceFirst;
 }
 
-extern "C" rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, int32_t n_tensors,
-                                              int32_t tp, rose_plan **out) {
+extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
+                                                  int32_t tp_src, int32_t src_rank, rose_plan **out) {
     if (!out) return ROSE_ERR_ARG;
     *out = nullptr;
-    if (!tensors || n_tensors < 1 || tp < 1) return ROSE_ERR_ARG;
-    if (tp > ROSE_MAX_TP) return ROSE_ERR_UNSUPPORTED;
+    if (!tensors || n_tensors < 1 || tp < 1 || tp_src < 1 || src_rank < 0 || src_rank >= tp_src) return ROSE_ERR_ARG;
+    if (tp > ROSE_MAX_TP || tp_src > ROSE_MAX_TP) return ROSE_ERR_UNSUPPORTED;
     for (int32_t i = 0; i < n_tensors; ++i) {
         rose_status s = check_desc(tensors[i], tp);
+        if (s == ROSE_OK) s = check_desc(tensors[i], tp_src);
         if (s != ROSE_OK) return s;
     }
     rose_plan *p = new (std::nothrow) rose_plan;
     if (!p) return ROSE_ERR_ARG;
     try {
         p->tp = tp;
+        p->tp_src = tp_src;
+        p->src_rank = src_rank;
         p->n_tensors = n_tensors;
         p->tensors.assign(tensors, tensors + n_tensors);
         p->global_base.resize(n_tensors + 1);
@@ -148,7 +180,7 @@ extern "C" rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, i
             p->chain_first[d] = (int32_t)n_tiles;
             for (int32_t i = 0; i < n_tensors; ++i) {
                 size_t first = p->pieces.size();
-                segment_pieces(tensors[i], i, d, tp, p->pieces);
+                segment_pieces(tensors[i], i, d, tp, tp_src, src_rank, p->pieces);
                 for (size_t k = first; k < p->pieces.size(); ++k) {
                     Piece &pc = p->pieces[k];
                     int64_t nt = pc.len == 0 ? 1 : ((int64_t)pc.len + rose::kTile - 1) / rose::kTile;
@@ -176,6 +208,11 @@ extern "C" rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, i
     return ROSE_OK;
 }
 
+extern "C" rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, int32_t n_tensors,
+                                              int32_t tp, rose_plan **out) {
+    return rose_shard_plan_create_src(tensors, n_tensors, tp, 1, 0, out);
+}
+
 extern "C" int32_t rose_plan_n_tensors(const rose_plan *p) { return p ? p->n_tensors : -1; }
 extern "C" int32_t rose_plan_tp(const rose_plan *p) { return p ? p->tp : -1; }
 
@@ -193,9 +230,16 @@ extern "C" rose_status rose_plan_local_numel(const rose_plan *p, int32_t t, int3
 
 extern "C" rose_status rose_plan_bucket_capacity(const rose_plan *p, int32_t d, int64_t *max_entries) {
     if (!p || !max_entries || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
-    int64_t s = 0;
-    for (const auto &t : p->tensors) s += local_numel(t, p->tp);
+    int64_t s = 0;                              // everything this sender can send to shard d
+    for (const Piece &pc : p->pieces)
+        if (pc.shard == d) s += pc.len;
     *max_entries = s;
+    return ROSE_OK;
+}
+
+extern "C" rose_status rose_plan_src_numel(const rose_plan *p, int32_t t, int64_t *numel) {
+    if (!p || !numel || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
+    *numel = local_numel(p->tensors[t], p->tp_src);
     return ROSE_OK;
 }
 
@@ -218,8 +262,7 @@ extern "C" rose_status rose_plan_workspace_bytes(const rose_plan *p, size_t *byt
 extern "C" rose_status rose_plan_map_index(const rose_plan *p, int32_t t, int64_t g, int32_t *d_first,
                                            int32_t *n_dest, int32_t *local) {
     if (!p || !d_first || !n_dest || !local || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
-    const rose_tensor_desc &td = p->tensors[t];
-    if (g < 0 || g >= td.rows * td.cols) return ROSE_ERR_ARG;
+    if (g < 0 || g >= local_numel(p->tensors[t], p->tp_src)) return ROSE_ERR_ARG;
     int found = 0;
     for (const Piece &pc : p->pieces) {
         if (pc.tensor != t || pc.len == 0) continue;
@@ -234,15 +277,22 @@ extern "C" rose_status rose_plan_map_index(const rose_plan *p, int32_t t, int64_
             k = rel;
         }
         if (k >= pc.len) continue;
+        int32_t loc = pc.local_base + (int32_t)k;
+        if (pc.flags & rose::kPieceDstStrided) loc = pc.local_base + (int32_t)((k / pc.run) * pc.lstride + k % pc.run);
         if (!found) {
             *d_first = pc.shard;
-            *local = pc.local_base + (int32_t)k;
-        } else if (*local != pc.local_base + (int32_t)k || pc.shard != *d_first + found) {
+            *local = loc;
+        } else if (*local != loc || pc.shard != *d_first + found) {
             return ROSE_ERR_ARG;   // tables inconsistent
         }
         ++found;
     }
-    if (!found) return ROSE_ERR_ARG;
+    if (!found) {
+        // a replicated tensor that another sender sends has no destination from here
+        if (sends(p->tensors[t], t, p->tp_src, p->src_rank)) return ROSE_ERR_ARG;
+        *d_first = 0;
+        *local = 0;
+    }
     *n_dest = found;
     return ROSE_OK;
 }

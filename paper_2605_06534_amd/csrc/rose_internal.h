@@ -28,14 +28,18 @@ constexpr int kTile = kThreads * kVec * kIters;    // elements per tile
 enum : int32_t {
     kPieceFirst = 1,    // first piece of its (tensor, shard) segment
     kPieceVec = 2,      // offsets and run lengths are multiples of kVec: 128-bit loads are legal
-    kPieceStrided = 4   // runs of `run` elements every `stride` source elements
+    kPieceStrided = 4,  // runs of `run` elements every `stride` source elements
+    kPieceDstStrided = 8 // runs of `run` elements every `lstride` LOCAL indices (the sender's slice
+                        // covers only part of each row of the destination shard)
 };
 
-// One run of a (tensor, shard) segment's local index space that maps to the source tensor
-// either contiguously or as equal runs at a fixed stride (a column block of a row-parallel
-// matrix).  Local index local_base + k  <->  source element
-//   src_off + k                                    (contiguous)
-//   src_off + (k / run) * stride + k % run         (strided)
+// One part of a (tensor, shard) segment: element k = 0 .. len-1 of the piece lies at
+//   source element  src_off + k                              (contiguous)
+//                   src_off + (k / run) * stride + k % run   (kPieceStrided: a column block of a
+//                                                             row-parallel matrix)
+//   local index     local_base + k                           (contiguous)
+//                   local_base + (k / run) * lstride + k % run   (kPieceDstStrided)
+// Both are ascending in k.
 struct Piece {
     int64_t src_off;
     int64_t stride;
@@ -48,7 +52,7 @@ struct Piece {
     uint32_t shift;
     int32_t first_tile;
     int32_t flags;
-    int32_t pad;
+    int32_t lstride;
 };
 static_assert(sizeof(Piece) == 56, "Piece layout is shared with device code");
 
@@ -124,6 +128,7 @@ int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chun
 }  // namespace rose
 
 struct rose_plan {
+    int32_t tp_src = 1, src_rank = 0;          // the sender holds shard src_rank of tp_src of every tensor
     int32_t tp = 0;
     int32_t n_tensors = 0;
     std::vector<rose_tensor_desc> tensors;

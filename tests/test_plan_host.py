@@ -55,6 +55,46 @@ def test_planner_tables_match_oracle_map(tp):
     assert plan.workspace_bytes() >= 8 * plan.n_tiles()
 
 
+@pytest.mark.parametrize("tp_src,tp", [(2, 4), (4, 2), (8, 4), (4, 1), (2, 2), (8, 8), (2, 8)])
+def test_sender_side_plan_matches_oracle_maps(tp_src, tp):
+    """Sender holds shard s of tp_src: element g of its slice is element (r, c) of the full tensor
+    (found by inverting the oracle's map for degree tp_src by brute force) and goes where the
+    oracle's map for degree tp sends (r, c)."""
+    shapes = [s for s in SHAPES if s[0] == R.REPLICATED or
+              (s[0] == R.SPLIT_ROWS and s[1] % 8 == 0) or (s[0] == R.SPLIT_COLS and s[2] % 8 == 0) or
+              (s[0] == R.FUSED_ROWS and all(x % 8 == 0 for x in s[3]))]
+    ts = [dict(name="t%d" % i, rows=r, cols=c, rule=rule, sections=sec) for i, (rule, r, c, sec) in enumerate(shapes)]
+    for s in range(tp_src):
+        plan = R.shard_plan(ts, tp, tp_src, s)
+        cap = [0] * tp
+        for i, t in enumerate(ts):
+            assert plan.src_numel(i) == oracle.local_numel(t["rule"], t["rows"], t["cols"], tp_src)
+            sends = t["rule"] != R.REPLICATED or i % tp_src == s
+            for r in range(t["rows"]):
+                for c in range(t["cols"]):
+                    s_first, n_src, g = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], tp_src, r, c)
+                    if not (s_first <= s < s_first + n_src):
+                        continue
+                    want = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], tp, r, c)
+                    got = plan.map_index(i, g)
+                    if sends:
+                        assert got == want, (s, i, r, c)
+                        for d in range(want[0], want[0] + want[1]):
+                            cap[d] += 1
+                    else:
+                        assert got[1] == 0
+        assert [plan.bucket_capacity(d) for d in range(tp)] == cap
+
+
+def test_sender_side_plan_argument_errors():
+    t = [dict(rows=8, cols=8, rule=R.SPLIT_ROWS, sections=None)]
+    for tp_src, rank, status in [(3, 0, binding.ERR_SHAPE), (2, 2, binding.ERR_ARG), (2, -1, binding.ERR_ARG),
+                                 (0, 0, binding.ERR_ARG), (32, 0, binding.ERR_UNSUPPORTED)]:
+        with pytest.raises(R.RoseError) as e:
+            R.shard_plan(t, 2, tp_src, rank)
+        assert e.value.status == status, (tp_src, rank)
+
+
 def test_large_shapes_sampled_against_oracle():
     ts = models.decoder(1, 5120, 40, 8, 128, 27648, 152064)
     plan = R.shard_plan(ts, 8)
