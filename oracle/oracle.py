@@ -207,3 +207,73 @@ def dense_shard(full, rows, cols, rule, sections, tp, d):
                                  out.ctypes.data)
     _check(rc, "dense_shard")
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Transport objects (Sec. 4.2 "Asynchronous Weight Transfer": senders push fixed-size buckets to a
+# relay, receivers pull what their metadata says they need).  A destination's entry stream is cut
+# into objects that carry their own description, so each can be applied alone and in any order.
+# The byte layout is this build's own (the paper fixes none); written out here by definition:
+#   0   u32 magic 0x45534F52, u32 version 1, i32 shard, i32 n_tensors
+#   16  i64 first_entry (position of the object's first entry in the shard's stream), i64 n_entries
+#   32  zero up to 64
+#   64  i64 seg_off[n_tensors + 1]: entries of tensor t are [seg_off[t], seg_off[t+1]) of THIS object
+#   A   i32 idx[n_entries]   A = 64 + 8 (n_tensors + 1) rounded up to 16
+#   B   u16 val[n_entries]   B = A + 4 n_entries rounded up to 16;  size = B + 2 n_entries rounded up to 16
+# ---------------------------------------------------------------------------------------------
+OBJECT_MAGIC = 0x45534F52
+
+
+def _up16(x):
+    return (x + 15) // 16 * 16
+
+
+def object_bytes(n_tensors, n_entries):
+    a = _up16(64 + 8 * (n_tensors + 1))
+    return a + _up16(4 * n_entries) + _up16(2 * n_entries)
+
+
+def pack_object(bucket, shard, first_entry, n_entries):
+    """bucket: dict idx, val, seg_off (a whole destination stream) -> the object's bytes (uint8)."""
+    seg = np.asarray(bucket["seg_off"], dtype=np.int64)
+    nt = seg.size - 1
+    total = int(seg[-1])
+    if first_entry < 0 or n_entries < 0 or first_entry + n_entries > total:
+        raise OracleError("object range outside the stream")
+    out = np.zeros(object_bytes(nt, n_entries), dtype=np.uint8)
+    out[0:8].view(np.uint32)[:] = (OBJECT_MAGIC, 1)
+    out[8:16].view(np.int32)[:] = (shard, nt)
+    out[16:32].view(np.int64)[:] = (first_entry, n_entries)
+    local = np.clip(seg - first_entry, 0, n_entries)
+    out[64:64 + 8 * (nt + 1)].view(np.int64)[:] = local
+    a = _up16(64 + 8 * (nt + 1))
+    b = a + _up16(4 * n_entries)
+    out[a:a + 4 * n_entries].view(np.int32)[:] = np.asarray(bucket["idx"], dtype=np.int32)[first_entry:first_entry + n_entries]
+    out[b:b + 2 * n_entries].view(np.uint16)[:] = np.asarray(bucket["val"], dtype=np.uint16)[first_entry:first_entry + n_entries]
+    return out
+
+
+def unpack_object(obj, n_tensors):
+    """Object bytes -> dict shard, first_entry, idx, val, seg_off; raises on a malformed object."""
+    obj = np.ascontiguousarray(obj, dtype=np.uint8)
+    if obj.size < 64 + 8 * (n_tensors + 1):
+        raise OracleError("object too short")
+    magic, version = (int(x) for x in obj[0:8].view(np.uint32))
+    shard, nt = (int(x) for x in obj[8:16].view(np.int32))
+    first, n = (int(x) for x in obj[16:32].view(np.int64))
+    if magic != OBJECT_MAGIC or version != 1 or nt != n_tensors or n < 0 or first < 0:
+        raise OracleError("bad object header")
+    if obj.size < object_bytes(nt, n):
+        raise OracleError("object shorter than its header says")
+    seg = obj[64:64 + 8 * (nt + 1)].view(np.int64).copy()
+    if seg[0] != 0 or seg[-1] != n or (np.diff(seg) < 0).any():
+        raise OracleError("bad segment table")
+    a = _up16(64 + 8 * (nt + 1))
+    b = a + _up16(4 * n)
+    return {"shard": shard, "first_entry": first, "seg_off": seg,
+            "idx": obj[a:a + 4 * n].view(np.int32).copy(), "val": obj[b:b + 2 * n].view(np.uint16).copy()}
+
+
+def apply_object(obj, n_tensors, dsts):
+    """Apply one object to the destination shard's tensors (list of uint16 arrays)."""
+    apply_bucket(unpack_object(obj, n_tensors), dsts)
