@@ -196,6 +196,41 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
                               int64_t *required);
 
 /*
+ * Transport objects (Sec. 4.2 "Asynchronous Weight Transfer": senders push fixed-size buckets to
+ * a relay, receivers pull the ones their metadata names).  A destination's entry stream is cut
+ * into objects that describe themselves, so that each can be applied alone, in any order.
+ * Layout of an object holding n entries of a plan with T tensors (little endian, this library's
+ * own format; all of it device memory, 16-byte aligned):
+ *     0  u32 magic ROSE_OBJECT_MAGIC, u32 version 1, i32 shard, i32 T
+ *    16  i64 first_entry (position of the object's first entry in the shard's stream), i64 n
+ *    32  zero up to 64
+ *    64  i64 seg_off[T + 1]: the entries of tensor t are [seg_off[t], seg_off[t+1]) of THIS object
+ *     A  i32 idx[n], A = 64 + 8 (T + 1) rounded up to 16
+ *     B  u16 val[n], B = A + 4 n rounded up to 16; size = B + 2 n rounded up to 16 (slack is zero)
+ *
+ * rose_object_bytes   size of an object with n_entries.
+ * rose_bucket_pack    writes entries [first_entry, first_entry + n_entries) of bucket d (as left by
+ *                     rose_delta_encode) into `object`.  The host checks sizes (ROSE_ERR_CAPACITY if
+ *                     object_bytes is too small); the range is checked against the bucket's true
+ *                     total on the device: a range beyond it yields an object with a zero magic,
+ *                     which nobody applies.
+ * rose_object_apply   checks the header on the device (magic, version, T, sizes against
+ *                     object_bytes, segment table ends) and applies the entries to the shard's
+ *                     tensors; an object that fails the check changes nothing.  Same rule as
+ *                     rose_delta_apply about concurrent writers of the destination.
+ * rose_object_check   synchronises `stream`, reads the header back and returns ROSE_ERR_ARG for a
+ *                     malformed object; shard / first_entry / n_entries (host, may be NULL).
+ */
+#define ROSE_OBJECT_MAGIC 0x45534F52u
+rose_status rose_object_bytes(const rose_plan *plan, int64_t n_entries, size_t *bytes);
+rose_status rose_bucket_pack(const rose_plan *plan, int32_t d, const rose_bucket *bucket, int64_t first_entry,
+                             int64_t n_entries, void *object, size_t object_bytes, void *stream);
+rose_status rose_object_apply(const rose_plan *plan, const void *object, size_t object_bytes,
+                              void *const *dst_ptrs, void *stream);
+rose_status rose_object_check(const rose_plan *plan, const void *object, size_t object_bytes, void *stream,
+                              int32_t *shard, int64_t *first_entry, int64_t *n_entries);
+
+/*
  * Bandwidth probe, for measuring what HBM delivers beside the kernels above: copies `bytes`
  * (a multiple of 16) from src to dst (device, 16-byte aligned); with dst = NULL it only reads
  * src; *sink (device, 8 bytes, required in that mode) exists so that the reads cannot be dropped

@@ -52,6 +52,10 @@ _SIGS = {
     "rose_delta_apply": (_i32, [_vp, _i32, _P(CBucket), _vp, _vp]),
     "rose_dense_copy": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp]),
     "rose_bucket_check": (_i32, [_vp, _P(CBucket), _vp, _P(_i64)]),
+    "rose_object_bytes": (_i32, [_vp, _i64, _P(ctypes.c_size_t)]),
+    "rose_bucket_pack": (_i32, [_vp, _i32, _P(CBucket), _i64, _i64, _vp, ctypes.c_size_t, _vp]),
+    "rose_object_apply": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
+    "rose_object_check": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _P(_i32), _P(_i64), _P(_i64)]),
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
     "rose_bw_probe_mixed": (_i32, [_vp, _vp, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp]),
     "rose_status_str": (ctypes.c_char_p, [_i32]),
@@ -227,3 +231,28 @@ def bw_probe_mixed(src_a, src_b, dst, write_bytes_per_chunk, sink, stream=None):
     nbytes = src_a.numel() * src_a.element_size()
     _check(_lib.rose_bw_probe_mixed(src_a.data_ptr(), src_b.data_ptr(), dst.data_ptr(), nbytes,
                                     write_bytes_per_chunk, sink.data_ptr(), _stream(stream)), "bw_probe_mixed")
+
+
+def object_bytes(plan, n_entries):
+    v = ctypes.c_size_t()
+    _check(_lib.rose_object_bytes(plan._h, n_entries, ctypes.byref(v)), "object_bytes")
+    return v.value
+
+
+def bucket_pack(plan, d, bucket, first_entry, n_entries, obj, stream=None):
+    """obj: uint8 device tensor of at least object_bytes(plan, n_entries)."""
+    cb = bucket.c()
+    _check(_lib.rose_bucket_pack(plan._h, d, ctypes.byref(cb), first_entry, n_entries, obj.data_ptr(),
+                                 obj.numel() * obj.element_size(), _stream(stream)), "bucket_pack")
+
+
+def object_apply(plan, obj, dst_tab, stream=None):
+    _check(_lib.rose_object_apply(plan._h, obj.data_ptr(), obj.numel() * obj.element_size(), dst_tab.data_ptr(),
+                                  _stream(stream)), "object_apply")
+
+
+def object_check(plan, obj, stream=None):
+    d, first, n = _i32(), _i64(), _i64()
+    _check(_lib.rose_object_check(plan._h, obj.data_ptr(), obj.numel() * obj.element_size(), _stream(stream),
+                                  ctypes.byref(d), ctypes.byref(first), ctypes.byref(n)), "object_check")
+    return d.value, first.value, n.value

@@ -167,3 +167,51 @@ extern "C" rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b,
                ? ROSE_OK
                : ROSE_ERR_HIP;
 }
+
+extern "C" rose_status rose_object_bytes(const rose_plan *p, int64_t n_entries, size_t *bytes) {
+    if (!p || !bytes || n_entries < 0) return ROSE_ERR_ARG;
+    *bytes = rose::object_bytes_for(p->n_tensors, n_entries);
+    return ROSE_OK;
+}
+
+extern "C" rose_status rose_bucket_pack(const rose_plan *p, int32_t d, const rose_bucket *bucket, int64_t first_entry,
+                                        int64_t n_entries, void *object, size_t object_bytes, void *stream) {
+    if (!p || !bucket || !object || d < 0 || d >= p->tp || first_entry < 0 || n_entries < 0) return ROSE_ERR_ARG;
+    rose_status s = check_bucket(*bucket);
+    if (s != ROSE_OK) return s;
+    if (!aligned(object, 16)) return ROSE_ERR_ALIGN;
+    if (first_entry + n_entries > bucket->capacity) return ROSE_ERR_ARG;
+    if (object_bytes < rose::object_bytes_for(p->n_tensors, n_entries)) return ROSE_ERR_CAPACITY;
+    rose::BucketDev b{bucket->idx, bucket->val, bucket->capacity, bucket->seg_off};
+    return rose::launch_pack(b, d, p->n_tensors, first_entry, n_entries, object, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_object_apply(const rose_plan *p, const void *object, size_t object_bytes,
+                                         void *const *dst_ptrs, void *stream) {
+    if (!p || !object || !dst_ptrs) return ROSE_ERR_ARG;
+    if (!aligned(object, 16) || !aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
+    if (object_bytes < rose::object_bytes_for(p->n_tensors, 0)) return ROSE_ERR_ARG;
+    const rose::Piece *pieces = nullptr;
+    const int32_t *tile_piece = nullptr, *local_numel = nullptr;
+    rose_status s = device_tables(p, &pieces, &tile_piece, &local_numel);
+    if (s != ROSE_OK) return s;
+    return rose::launch_apply_object(object, object_bytes, p->n_tensors, local_numel, dst_ptrs, stream) == 0
+               ? ROSE_OK
+               : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_object_check(const rose_plan *p, const void *object, size_t object_bytes, void *stream,
+                                         int32_t *shard, int64_t *first_entry, int64_t *n_entries) {
+    if (!p || !object || object_bytes < 64) return ROSE_ERR_ARG;
+    uint32_t h[16];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(h, object, sizeof h, hipMemcpyDeviceToHost, st) != hipSuccess) return ROSE_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return ROSE_ERR_HIP;
+    int64_t n = 0;
+    if (!rose::object_header_valid(h, p->n_tensors, object_bytes, &n)) return ROSE_ERR_ARG;
+    if ((int32_t)h[2] < 0 || (int32_t)h[2] >= p->tp) return ROSE_ERR_ARG;
+    if (shard) *shard = (int32_t)h[2];
+    if (first_entry) *first_entry = (int64_t)((uint64_t)h[4] | ((uint64_t)h[5] << 32));
+    if (n_entries) *n_entries = n;
+    return ROSE_OK;
+}

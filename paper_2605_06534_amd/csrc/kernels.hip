@@ -1187,8 +1187,8 @@ __device__ __forceinline__ int32_t wave_find_segment(const int64_t *seg_off, int
     return lo;
 }
 
-__global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors,
-                                                              const int32_t *local_numel, void *const *dst_ptrs) {
+__device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel,
+                                           void *const *dst_ptrs) {
     __shared__ uint4 s_line[kApplyWaves][64][4];        // wave, line slot, 16-byte part
     __shared__ u64 s_addr[kApplyWaves][64];             // address of the line
     __shared__ int32_t s_parts[kApplyWaves][64];        // 16-byte parts of the line inside the tensor
@@ -1299,6 +1299,88 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32
 #endif
         lds_wave_fence();                               // the LDS slots are reused by the next round
     }
+}
+
+__global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors,
+                                                              const int32_t *local_numel, void *const *dst_ptrs) {
+    apply_body(b, n_tensors, local_numel, dst_ptrs);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transport objects (Sec. 4.2 "Asynchronous Weight Transfer": fixed-size buckets that describe
+// themselves): a range of a destination's entries with a header and its own segment table, see
+// the layout in the header file.  pack copies; apply checks the header on the device and then
+// runs the ordinary apply on the arrays inside the object.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline size_t up16(size_t x) { return (x + 15) & ~(size_t)15; }
+__host__ __device__ inline size_t object_idx_off(int32_t n_tensors) { return up16(64 + 8 * ((size_t)n_tensors + 1)); }
+__host__ __device__ inline size_t object_size(int32_t n_tensors, int64_t n) {
+    return object_idx_off(n_tensors) + up16(4 * (size_t)n) + up16(2 * (size_t)n);
+}
+
+__global__ __launch_bounds__(256) void pack_kernel(BucketDev b, int32_t shard, int32_t n_tensors, int64_t first,
+                                                   int64_t n, char *obj) {
+    int64_t total = b.seg_off[n_tensors];
+    if (total > b.capacity) total = b.capacity;
+    const bool ok = total >= 0 && first + n <= total;          // else: an object nobody will apply
+    const size_t a_off = object_idx_off(n_tensors), b_off = a_off + up16(4 * (size_t)n);
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < 16) {
+            uint32_t w = 0;
+            if (threadIdx.x == 0) w = ok ? ROSE_OBJECT_MAGIC : 0u;
+            if (threadIdx.x == 1) w = 1u;
+            if (threadIdx.x == 2) w = (uint32_t)shard;
+            if (threadIdx.x == 3) w = (uint32_t)n_tensors;
+            if (threadIdx.x == 4) w = (uint32_t)(u64)first;
+            if (threadIdx.x == 5) w = (uint32_t)((u64)first >> 32);
+            if (threadIdx.x == 6) w = (uint32_t)(u64)n;
+            if (threadIdx.x == 7) w = (uint32_t)((u64)n >> 32);
+            reinterpret_cast<uint32_t *>(obj)[threadIdx.x] = w;
+        }
+        int64_t *seg = reinterpret_cast<int64_t *>(obj + 64);
+        for (int32_t t = threadIdx.x; t <= n_tensors; t += blockDim.x) {
+            int64_t v = b.seg_off[t] - first;
+            seg[t] = v < 0 ? 0 : (v > n ? n : v);
+        }
+        // the index and value arrays end on 16-byte boundaries: zero the slack
+        int32_t *idx = reinterpret_cast<int32_t *>(obj + a_off);
+        uint16_t *val = reinterpret_cast<uint16_t *>(obj + b_off);
+        if (threadIdx.x < 4 && n + threadIdx.x < (int64_t)(up16(4 * (size_t)n) / 4)) idx[n + threadIdx.x] = 0;
+        if (threadIdx.x < 8 && n + threadIdx.x < (int64_t)(up16(2 * (size_t)n) / 2)) val[n + threadIdx.x] = 0;
+    }
+    if (!ok) return;
+    int32_t *idx = reinterpret_cast<int32_t *>(obj + a_off);
+    uint16_t *val = reinterpret_cast<uint16_t *>(obj + b_off);
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+        idx[e] = b.idx[first + e];
+        val[e] = b.val[first + e];
+    }
+}
+
+// true if the 64-byte header describes an object of this plan that fits object_bytes
+__host__ __device__ inline bool object_header_ok(const uint32_t *h, int32_t n_tensors, size_t object_bytes, int64_t *n_out) {
+    const int64_t first = (int64_t)((u64)h[4] | ((u64)h[5] << 32));
+    const int64_t n = (int64_t)((u64)h[6] | ((u64)h[7] << 32));
+    *n_out = n;
+    if (h[0] != ROSE_OBJECT_MAGIC || h[1] != 1u || (int32_t)h[3] != n_tensors || first < 0 || n < 0) return false;
+    if (n > (int64_t)(object_bytes / 6)) return false;
+    return object_size(n_tensors, n) <= object_bytes;
+}
+
+__global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char *obj, size_t object_bytes, int32_t n_tensors,
+                                                                     const int32_t *local_numel, void *const *dst_ptrs) {
+    uint32_t h[8];
+    for (int i = 0; i < 8; ++i) h[i] = reinterpret_cast<const uint32_t *>(obj)[i];
+    int64_t n;
+    if (!object_header_ok(h, n_tensors, object_bytes, &n)) return;     // uniform: every thread leaves
+    const size_t a_off = object_idx_off(n_tensors), b_off = a_off + up16(4 * (size_t)n);
+    BucketDev b;
+    b.idx = reinterpret_cast<int32_t *>(const_cast<char *>(obj + a_off));
+    b.val = reinterpret_cast<uint16_t *>(const_cast<char *>(obj + b_off));
+    b.capacity = n;
+    b.seg_off = reinterpret_cast<int64_t *>(const_cast<char *>(obj + 64));
+    if (b.seg_off[0] != 0 || b.seg_off[n_tensors] != n) return;
+    apply_body(b, n_tensors, local_numel, dst_ptrs);
 }
 
 #ifdef ROSE_APPLY_SCATTER
@@ -1517,6 +1599,29 @@ int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_num
     hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs);
 #endif
     return (int)hipGetLastError();
+}
+
+int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, void *object, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int64_t want = (n + 1023) / 1024;
+    int blocks = want < 1 ? 1 : (want > 256 * 16 ? 256 * 16 : (int)want);
+    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, b, shard, n_tensors, first, n, static_cast<char *>(object));
+    return (int)hipGetLastError();
+}
+
+int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, const int32_t *local_numel,
+                        void *const *dst_ptrs, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int64_t chunks = ((int64_t)(object_bytes / 6) + kApplyThreads - 1) / kApplyThreads;
+    int blocks = chunks < 1 ? 1 : (chunks > 256 * 32 ? 256 * 32 : (int)chunks);
+    hipLaunchKernelGGL(apply_object_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, static_cast<const char *>(object),
+                       object_bytes, n_tensors, local_numel, dst_ptrs);
+    return (int)hipGetLastError();
+}
+
+size_t object_bytes_for(int32_t n_tensors, int64_t n) { return object_size(n_tensors, n); }
+bool object_header_valid(const uint32_t *h, int32_t n_tensors, size_t object_bytes, int64_t *n) {
+    return object_header_ok(h, n_tensors, object_bytes, n);
 }
 
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream) {

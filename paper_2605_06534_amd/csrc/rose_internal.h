@@ -121,6 +121,11 @@ int launch_encode(const EncodeArgs &a, int new_is_f32, void *stream);
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
                  void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
+int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, void *object, void *stream);
+int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, const int32_t *local_numel,
+                        void *const *dst_ptrs, void *stream);
+size_t object_bytes_for(int32_t n_tensors, int64_t n);
+bool object_header_valid(const uint32_t *header, int32_t n_tensors, size_t object_bytes, int64_t *n);
 int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
 int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, uint64_t *sink,
                           void *stream);
