@@ -166,6 +166,23 @@ rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs
                               void *stream);
 
 /*
+ * delta_encode with sender refresh (Sec. 4.2: the sender keeps W_{t-1} resident and makes it
+ * current for the next step): the same buckets as rose_delta_encode, and afterwards every old
+ * tensor the sender holds equals the new one as bf16 (for fp32 input: its round-to-nearest-even
+ * cast), so that the same old tensors serve the next step while the new ones may be overwritten by
+ * the trainer.  Only the 16-byte vectors that contain a change are written (whole replicated
+ * tensors, which are small, are copied by a second kernel once every destination has read them).
+ * old_ptrs' tensors are WRITTEN; everything else as rose_delta_encode.  If the launch gives up
+ * (see above) or a bucket overflows, old is already partly refreshed and the dropped entries
+ * cannot be produced again from it: size buckets for the worst case when using this call, or
+ * keep the new weights until rose_bucket_check has passed.
+ */
+rose_status rose_delta_encode_refresh(const rose_plan *plan, void *const *old_ptrs,
+                                      const void *const *new_ptrs, int32_t new_dtype,
+                                      const rose_bucket *buckets, void *workspace, size_t workspace_bytes,
+                                      void *stream);
+
+/*
  * delta_apply (Sec. 4.2 "each device applies only its local shard", App. F S2D): writes every
  * entry's value at its local index of shard d's resident copies.
  *   bucket    HOST struct, device arrays as written by rose_delta_encode for shard d

@@ -49,6 +49,7 @@ _SIGS = {
     "rose_plan_workspace_bytes": (_i32, [_vp, _P(ctypes.c_size_t)]),
     "rose_plan_n_tiles": (_i32, [_vp, _P(_i64)]),
     "rose_delta_encode": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
+    "rose_delta_encode_refresh": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
     "rose_delta_apply": (_i32, [_vp, _i32, _P(CBucket), _vp, _vp]),
     "rose_dense_copy": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp]),
     "rose_bucket_check": (_i32, [_vp, _P(CBucket), _vp, _P(_i64)]),
@@ -196,6 +197,14 @@ def delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=None):
     _check(_lib.rose_delta_encode(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, cb,
                                   ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
            "delta_encode")
+
+
+def delta_encode_refresh(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=None):
+    """delta_encode that also makes the old tensors equal to the new ones (as bf16)."""
+    cb = (CBucket * plan.tp)(*[b.c() for b in buckets])
+    _check(_lib.rose_delta_encode_refresh(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, cb,
+                                          ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
+           "delta_encode_refresh")
 
 
 def delta_apply(plan, d, bucket, dst_tab, stream=None):

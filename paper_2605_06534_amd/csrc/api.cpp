@@ -24,6 +24,16 @@ rose_status device_tables(const rose_plan *p, const rose::Piece **pieces, const 
             const rose_tensor_desc &t = p->tensors[i];
             numel[i] = (int32_t)(t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : p->tp));
         }
+        std::vector<int32_t> repl;
+        std::vector<int64_t> repl_numel;
+        for (int32_t i = 0; i < p->n_tensors; ++i) {
+            if (p->tensors[i].rule == ROSE_REPLICATED && p->tensors[i].rows * p->tensors[i].cols > 0) {
+                repl.push_back(i);
+                repl_numel.push_back(p->tensors[i].rows * p->tensors[i].cols);
+            }
+        }
+        int32_t *dr = nullptr;
+        int64_t *drn = nullptr;
         size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
         size_t nb = numel.size() * sizeof(int32_t);
         bool ok = hipMalloc(reinterpret_cast<void **>(&dp), pb) == hipSuccess &&
@@ -32,15 +42,26 @@ rose_status device_tables(const rose_plan *p, const rose::Piece **pieces, const 
                   hipMemcpy(dp, p->pieces.data(), pb, hipMemcpyHostToDevice) == hipSuccess &&
                   hipMemcpy(dt, p->tile_piece.data(), tb, hipMemcpyHostToDevice) == hipSuccess &&
                   hipMemcpy(dn, numel.data(), nb, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok && !repl.empty()) {
+            ok = hipMalloc(reinterpret_cast<void **>(&dr), repl.size() * sizeof(int32_t)) == hipSuccess &&
+                 hipMalloc(reinterpret_cast<void **>(&drn), repl.size() * sizeof(int64_t)) == hipSuccess &&
+                 hipMemcpy(dr, repl.data(), repl.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+                 hipMemcpy(drn, repl_numel.data(), repl.size() * sizeof(int64_t), hipMemcpyHostToDevice) == hipSuccess;
+        }
         if (!ok) {
             if (dp) (void)hipFree(dp);
             if (dt) (void)hipFree(dt);
             if (dn) (void)hipFree(dn);
+            if (dr) (void)hipFree(dr);
+            if (drn) (void)hipFree(drn);
             return ROSE_ERR_HIP;
         }
         p->d_pieces = dp;
         p->d_tile_piece = dt;
         p->d_local_numel = dn;
+        p->d_repl_list = dr;
+        p->d_repl_numel = drn;
+        p->n_repl = (int32_t)repl.size();
         p->device = dev;
     } else if (p->device != dev) {
         return ROSE_ERR_ARG;
@@ -65,13 +86,14 @@ extern "C" void rose_shard_plan_destroy(rose_plan *p) {
     if (p->d_pieces) (void)hipFree(p->d_pieces);
     if (p->d_tile_piece) (void)hipFree(p->d_tile_piece);
     if (p->d_local_numel) (void)hipFree(p->d_local_numel);
+    if (p->d_repl_list) (void)hipFree(p->d_repl_list);
+    if (p->d_repl_numel) (void)hipFree(p->d_repl_numel);
     delete p;
 }
 
-extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *old_ptrs,
-                                         const void *const *new_ptrs, int32_t new_dtype,
-                                         const rose_bucket *buckets, void *workspace,
-                                         size_t workspace_bytes, void *stream) {
+static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs, const void *const *new_ptrs,
+                                 int32_t new_dtype, const rose_bucket *buckets, void *workspace,
+                                 size_t workspace_bytes, bool refresh, void *stream) {
     if (!p || !old_ptrs || !new_ptrs || !buckets || !workspace) return ROSE_ERR_ARG;
     if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
     size_t need = 0;
@@ -103,7 +125,24 @@ extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *
     a.block_desc = a.tile_desc + a.n_tiles;
     a.tp = p->tp;
     a.n_tensors = p->n_tensors;
-    return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+    rose::RefreshArgs r{p->d_repl_list, p->d_repl_numel, p->n_repl};
+    return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, refresh ? &r : nullptr, stream) == 0 ? ROSE_OK
+                                                                                                  : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *old_ptrs,
+                                         const void *const *new_ptrs, int32_t new_dtype,
+                                         const rose_bucket *buckets, void *workspace,
+                                         size_t workspace_bytes, void *stream) {
+    return encode_common(p, old_ptrs, new_ptrs, new_dtype, buckets, workspace, workspace_bytes, false, stream);
+}
+
+extern "C" rose_status rose_delta_encode_refresh(const rose_plan *p, void *const *old_ptrs,
+                                                 const void *const *new_ptrs, int32_t new_dtype,
+                                                 const rose_bucket *buckets, void *workspace,
+                                                 size_t workspace_bytes, void *stream) {
+    return encode_common(p, const_cast<const void *const *>(old_ptrs), new_ptrs, new_dtype, buckets, workspace,
+                         workspace_bytes, true, stream);
 }
 
 extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const rose_bucket *bucket,

@@ -69,6 +69,13 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
 #ifndef ROSE_NT_LOADS
 #define ROSE_NT_LOADS 1
 #endif
+#ifndef ROSE_REFRESH_NT
+#define ROSE_REFRESH_NT 1
+#endif
+#ifndef ROSE_REFRESH_WHOLE
+#define ROSE_REFRESH_WHOLE 160         // entries per tile above which refresh rewrites the whole tile
+                                       // (7B workload: 7.7 ms at 1 %, 8.0 ms at 5 %; 10.7 ms at 5 % without)
+#endif
 #ifndef ROSE_NT_STORES
 #define ROSE_NT_STORES 1
 #endif
@@ -455,7 +462,7 @@ struct TileMeta {
     int32_t shard;
     int32_t seg;        // tensor whose segment starts with this tile, else -1
     uint32_t limit;     // see load_raw
-    uint32_t vec;
+    uint32_t vec;       // bit 0: 128-bit loads are legal; bit 1: piece of a replicated tensor
     uint32_t k_tile;
 };
 __device__ __forceinline__ TileMeta tile_meta(const TileCtx &c, int32_t tile) {
@@ -466,7 +473,7 @@ __device__ __forceinline__ TileMeta tile_meta(const TileCtx &c, int32_t tile) {
     m.shard = c.pc.shard;
     m.seg = ((c.pc.flags & kPieceFirst) && tile == c.pc.first_tile) ? c.pc.tensor : -1;
     m.limit = c.limit;
-    m.vec = c.vec;
+    m.vec = c.vec | ((c.pc.flags & kPieceReplicated) ? 2u : 0u);
     m.k_tile = c.k_tile;
     return m;
 }
@@ -582,7 +589,7 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
     }
 }
 
-template <int NEW_F32>
+template <int NEW_F32, int REFRESH>
 __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     __shared__ uint32_t s_ring[kRing];      // an entry: offset inside its tile << 16 | value
     __shared__ uint32_t s_wave_total[2][kWaves];
@@ -851,7 +858,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 #pragma unroll
         for (int j = 0; j < kIters; ++j)
             asm volatile("" : "+v"(mask[j]), "+v"(nv[j].x), "+v"(nv[j].y), "+v"(nv[j].z), "+v"(nv[j].w));
-        if (cur.vec) {
+        if (cur.vec & 1u) {
             if (cur.limit != 0xFFFFFFFFu) {            // vectors past the end of the piece hold nothing
 #pragma unroll
                 for (int j = 0; j < kIters; ++j)
@@ -1075,6 +1082,42 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             __syncthreads();                           // s_direct_excl / s_ok are reused
         }
 
+        // Sender refresh (W_{t-1} <- W_t for what this tile covers): only now that the tile is known
+        // not to be walked again, and never for replicated tensors, which other destinations' tiles
+        // still have to read (a small kernel after this one copies those).
+        if constexpr (REFRESH) {
+            if (!skip && !(cur.vec & 2u)) {
+                const TileCtx c = tile_ctx(a, __builtin_amdgcn_readfirstlane(tile));
+                uint16_t *ob = const_cast<uint16_t *>(c.old_base);
+                // a tile with many changes is written whole: full lines cost the memory less than
+                // many partial ones
+                const bool whole = (cur.vec & 1u) && c.limit == 0xFFFFFFFFu && tile_total > (uint32_t)ROSE_REFRESH_WHOLE;
+#pragma unroll
+                for (int j = 0; j < kIters; ++j) {
+                    if (mask[j] || whole) {
+                        const uint32_t k = c.k_tile + t_off + (uint32_t)(j * 64) * kVec;
+                        if ((cur.vec & 1u) && (c.limit == 0xFFFFFFFFu || k + kVec <= c.limit)) {
+#if ROSE_REFRESH_NT
+                            {
+                                u32x4 w = {nv[j].x, nv[j].y, nv[j].z, nv[j].w};
+                                __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(ob + src_index(c.pc, k, true))));
+                            }
+#else
+                            gstore16(ob + src_index(c.pc, k, true), nv[j]);     // unchanged elements keep their bits
+#endif
+                        } else {
+                            uint32_t m = mask[j];
+                            while (m) {
+                                const uint32_t e = __ffs(m) - 1;
+                                m &= m - 1;
+                                ob[src_index(c.pc, k + e, false)] = (uint16_t)pick16(nv[j], e);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+
         // The rare cases that the next tile could not be named before the barrier above, or that a
         // same-group ticket has arrived: settle them now; the next tile's loads are then issued at
         // the top of the next iteration.
@@ -1124,18 +1167,43 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     while (q_len > 0) drain(true);
 }
 
-// The two instantiations get their own register budgets: 4 waves per SIMD (128 VGPRs) fit the
-// bf16 kernel without spills, the fp32-master kernel holds twice the raw data and gets 3.
-template <int NEW_F32> __global__ void encode_kernel(EncodeArgs a);
+// The instantiations get their own register budgets: 4 waves per SIMD (128 VGPRs) fit the bf16
+// kernel without spills, the fp32-master kernel holds twice the raw data and gets 3.  REFRESH = 1
+// also writes the new bf16 values over the old ones (rose_delta_encode_refresh).
+template <int NEW_F32, int REFRESH> __global__ void encode_kernel(EncodeArgs a);
 template <>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4), amdgpu_num_vgpr(kNumVgprBf16)))
-void encode_kernel<0>(EncodeArgs a) {
-    encode_body<0>(a);
+void encode_kernel<0, 0>(EncodeArgs a) {
+    encode_body<0, 0>(a);
+}
+template <>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4), amdgpu_num_vgpr(kNumVgprBf16)))
+void encode_kernel<0, 1>(EncodeArgs a) {
+    encode_body<0, 1>(a);
 }
 template <>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3), amdgpu_num_vgpr(kNumVgprF32)))
-void encode_kernel<1>(EncodeArgs a) {
-    encode_body<1>(a);
+void encode_kernel<1, 0>(EncodeArgs a) {
+    encode_body<1, 0>(a);
+}
+template <>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3), amdgpu_num_vgpr(kNumVgprF32)))
+void encode_kernel<1, 1>(EncodeArgs a) {
+    encode_body<1, 1>(a);
+}
+
+// Replicated tensors after an encode with refresh: old <- bf16(new), whole tensors (they are small).
+__global__ __launch_bounds__(256) void refresh_replicated_kernel(const int32_t *list, const int64_t *numel, int32_t n,
+                                                                 void *const *old_ptrs, const void *const *new_ptrs,
+                                                                 int new_is_f32) {
+    for (int32_t i = blockIdx.y; i < n; i += gridDim.y) {
+        const int32_t t = list[i];
+        uint16_t *o = static_cast<uint16_t *>(old_ptrs[t]);
+        const int64_t cnt = numel[i];
+        for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < cnt; k += (int64_t)gridDim.x * blockDim.x)
+            o[k] = new_is_f32 ? (uint16_t)rne_bf16(static_cast<const uint32_t *>(new_ptrs[t])[k])
+                              : static_cast<const uint16_t *>(new_ptrs[t])[k];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1523,15 +1591,18 @@ __global__ __launch_bounds__(256) void bw_mix_kernel(const uint4 *a, const uint4
 #endif
 
 // Number of workgroups that fit on the device at once for the encode kernel.
-static int encode_resident(int new_is_f32, int *resident) {
-    static int cached[2] = {0, 0};          // per kernel variant; the device set is homogeneous
+static int encode_resident(int new_is_f32, int refresh, int *resident) {
+    static int cached_all[4] = {0, 0, 0, 0};      // per kernel variant; the device set is homogeneous
+    int *cached = cached_all + 2 * refresh;
     if (!cached[new_is_f32]) {
         int dev = 0, cus = 0, per_cu = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = new_is_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<1>, kThreads, 0)
-                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<0>, kThreads, 0);
+            e = refresh ? (new_is_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<1, 1>, kThreads, 0)
+                                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<0, 1>, kThreads, 0))
+                        : (new_is_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<1, 0>, kThreads, 0)
+                                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<0, 0>, kThreads, 0));
         if (e != hipSuccess) return (int)e;
         if (per_cu < 1 || cus < 1) return (int)hipErrorInvalidValue;
         if (per_cu > ROSE_WGS_PER_CU) per_cu = ROSE_WGS_PER_CU;
@@ -1545,11 +1616,11 @@ static int encode_resident(int new_is_f32, int *resident) {
 #define ROSE_SERVER_WGS 16          // workgroups of the grid that serve prefixes (kWaves servers each)
 #endif
 
-int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
+int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     EncodeArgs a = args;
     int resident = 0;
-    int rc = encode_resident(new_is_f32, &resident);
+    int rc = encode_resident(new_is_f32, refresh ? 1 : 0, &resident);
     if (rc) return rc;
     // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
     // a quarter of what is resident.  They are the first workgroups of the grid, so they are
@@ -1580,10 +1651,18 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, void *stream) {
     int reset_blocks = (int)((n_words + 1023) / 1024);
     if (reset_blocks > 2048) reset_blocks = 2048;
     hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, reinterpret_cast<u64 *>(a.abort_flag), n_words);
-    if (new_is_f32)
-        hipLaunchKernelGGL(encode_kernel<1>, dim3(workers + server_wgs), dim3(kThreads), 0, st, a);
-    else
-        hipLaunchKernelGGL(encode_kernel<0>, dim3(workers + server_wgs), dim3(kThreads), 0, st, a);
+    const dim3 grid(workers + server_wgs), block(kThreads);
+    if (refresh) {
+        if (new_is_f32) hipLaunchKernelGGL((encode_kernel<1, 1>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((encode_kernel<0, 1>), grid, block, 0, st, a);
+        if (refresh->n > 0)
+            hipLaunchKernelGGL(refresh_replicated_kernel, dim3(8, refresh->n > 1024 ? 1024 : refresh->n), dim3(256), 0, st,
+                               refresh->list, refresh->numel, refresh->n, const_cast<void *const *>(a.old_ptrs),
+                               a.new_ptrs, new_is_f32);
+    } else {
+        if (new_is_f32) hipLaunchKernelGGL((encode_kernel<1, 0>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((encode_kernel<0, 0>), grid, block, 0, st, a);
+    }
     hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, st, a);
     return (int)hipGetLastError();
 }

@@ -118,7 +118,10 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
     int64_t lo, hi;
     if (sends(t, ti, S, s)) {
         switch (t.rule) {
-        case ROSE_REPLICATED: add(0, R * C, 0, R * C, R * C, R * C); break;
+        case ROSE_REPLICATED:
+            add(0, R * C, 0, R * C, R * C, R * C);
+            if (out.size() > first) out.back().flags |= rose::kPieceReplicated;
+            break;
         case ROSE_SPLIT_ROWS:
             if (overlap(s * (R / S), (s + 1) * (R / S), d * (R / D), (d + 1) * (R / D), &lo, &hi))
                 add((lo - s * (R / S)) * C, 0, (lo - d * (R / D)) * C, 0, (hi - lo) * C, (hi - lo) * C);

@@ -29,6 +29,7 @@ enum : int32_t {
     kPieceFirst = 1,    // first piece of its (tensor, shard) segment
     kPieceVec = 2,      // offsets and run lengths are multiples of kVec: 128-bit loads are legal
     kPieceStrided = 4,  // runs of `run` elements every `stride` source elements
+    kPieceReplicated = 16, // piece of a replicated tensor: several destinations read the same source
     kPieceDstStrided = 8 // runs of `run` elements every `lstride` LOCAL indices (the sender's slice
                         // covers only part of each row of the destination shard)
 };
@@ -117,7 +118,13 @@ inline uint32_t magic_div(uint32_t k, uint32_t magic, uint32_t shift) {
 }
 
 // kernel launchers (kernels.hip); all return a hipError_t as int
-int launch_encode(const EncodeArgs &a, int new_is_f32, void *stream);
+// replicated tensors to copy new -> old after an encode with refresh (device arrays of n entries)
+struct RefreshArgs {
+    const int32_t *list;
+    const int64_t *numel;
+    int32_t n;
+};
+int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, void *stream);
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
                  void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
@@ -148,4 +155,7 @@ struct rose_plan {
     mutable rose::Piece *d_pieces = nullptr;
     mutable int32_t *d_tile_piece = nullptr;
     mutable int32_t *d_local_numel = nullptr;  // [n_tensors] elements of a shard's copy of each tensor
+    mutable int32_t *d_repl_list = nullptr;    // replicated tensors (ordinals) and their sizes
+    mutable int64_t *d_repl_numel = nullptr;
+    mutable int32_t n_repl = 0;
 };
