@@ -1,6 +1,7 @@
 // HIP kernels for gfx950 (wave64): diff + mask + count + scan + shard-aware bucket write
 // (Sec. 4.2 "Sparsity-aware Weight Transfer", App. F D2S), scatter-apply (App. F S2D), the dense
-// shard copy (Sec. 4.2 "Shard-aware Weight Transfer") and a bandwidth probe.
+// shard copy (Sec. 4.2 "Shard-aware Weight Transfer"), transport objects (Sec. 4.2 "Asynchronous
+// Weight Transfer") and bandwidth probes.
 //
 // Everything here is bound by HBM traffic; there is no contraction, so no MFMA.  The encode
 // kernel reads each weight once with 128-bit loads and writes only the changed entries.
@@ -402,22 +403,21 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 // w, w + n_workers, ...), the remaining ones serve prefixes (above).
 //
 // Worker, per tile: (1) the tile's 128-bit loads were issued one tile earlier; XOR old and new
-// into an 8-bit change mask per vector, (2) issue the NEXT tile's loads, (3) wave prefix sums of
-// the popcounts, wave totals through LDS, (4) publish the tile's count, (5) park the tile's
-// entries, compacted, in an LDS ring and go on.  The wait for a tile's prefix is deferred: only
-// when the ring (kRing entries) or the queue of parked tiles (kQueue) is full, and at the end, are
-// the parked tiles' prefixes collected (one lane per parked tile, all polled together) and their
-// entries copied to the buckets with contiguous stores.  This keeps loads in flight while counts
-// travel between workgroups.  A tile with more than kRing entries is written straight from
+// into an 8-bit change mask per vector, (2) copy out parked tiles whose prefixes have arrived,
+// poll for the others, ask for a ticket, (3) issue the NEXT tile's loads, (4) wave prefix sums of
+// the popcounts, wave totals through LDS, (5) publish the tile's count, (6) park the tile's
+// entries, compacted, in an LDS ring and go on (the order of the memory operations matters: see
+// the comment in encode_body).  The wait for a tile's prefix is deferred: parked tiles are polled
+// one lane per tile, every iteration, without waiting; only when the ring (kRing entries) or the
+// queue of parked tiles (kQueue) is full, and at the end, does a workgroup wait.  This keeps
+// loads in flight while counts travel between workgroups.  A tile with more than kRing entries
+// (only possible if the ring is configured smaller than a tile) is written straight from
 // registers after a drain.
 // Inside a tile wave w covers a contiguous part and walks it in kIters steps of 512 elements,
 // so the order (wave, step, lane, element) is ascending local index.
 // ---------------------------------------------------------------------------------------------
 #ifndef ROSE_RING
 #define ROSE_RING 8192
-#endif
-#ifndef ROSE_WAVES_PER_EU
-#define ROSE_WAVES_PER_EU 4     // register budget of the encode kernel: 512 / 4 = 128 VGPRs
 #endif
 #ifndef ROSE_QUEUE
 #define ROSE_QUEUE 16
