@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--src-rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=float, default=4.0e9)
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a HIP graph (for launch-bound small workloads); the per-kernel "
+                         "times in `detail` are still taken from eager launches")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per encode launch from rocprofv3 counters, to report as roofline.traffic")
     return ap.parse_args()
@@ -149,6 +152,22 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    if args.graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(max(args.warmup, 1)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     t_enc = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps      # ms, HIP events on the launch stream
     t_app = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
 
@@ -231,7 +250,7 @@ def main():
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": args.workload, "elements": n_elems, "tensors": len(tensors), "tp": tp,
                    "recipe": recipe, "density": p, "nnz": nnz_total, "seed": args.seed,
-                   "tp_src": args.tp_src, "src_rank": args.src_rank,
+                   "tp_src": args.tp_src, "src_rank": args.src_rank, "hip_graph": bool(args.graph),
                    "new_dtype": "fp32->bf16 RNE" if new_dtype == R.FP32_RNE else "bf16"},
         "roofline": {"bound": "hbm", "kernel": "encode_kernel",
                      "achieved": round(enc_bytes / 1e9 / (t_enc / 1e3), 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
