@@ -54,7 +54,7 @@ def _load():
         lib.orc_encode_tensor.restype = i32
         lib.orc_encode_tensor.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, vp, vp, vp]
         lib.orc_encode_tensor_src.restype = i32
-        lib.orc_encode_tensor_src.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, i32, i32, i32, vp, vp, vp]
+        lib.orc_encode_tensor_src.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         lib.orc_apply.restype = i32
         lib.orc_apply.argtypes = [vp, vp, i64, vp, i64]
         lib.orc_dense_shard.restype = i32
@@ -135,9 +135,10 @@ def encode_tensor(old, new, rows, cols, rule, sections, tp):
 
 
 def encode_tensor_src(old_slice, new_slice, rows, cols, rule, sections, tp_dst, tp_src, src_rank,
-                      sends_replicated=True):
+                      sends_replicated=True, src_groups=0):
     """Dense-to-sparse of one tensor by the sender that holds shard `src_rank` of `tp_src` of it
-    (rows, cols are the FULL tensor's) -> list over destination shards of (idx int32, val uint16)."""
+    (rows, cols are the FULL tensor's) -> list over destination shards of (idx int32, val uint16).
+    src_groups = G > 0: the sender side keeps a fused tensor interleaved by G head groups."""
     lib = _load()
     old = np.ascontiguousarray(old_slice).view(np.uint16).ravel()
     new = np.ascontiguousarray(new_slice).ravel()
@@ -151,7 +152,8 @@ def encode_tensor_src(old_slice, new_slice, rows, cols, rule, sections, tp_dst, 
     if old.size != want or new.size != want:
         raise OracleError("slice sizes do not match the sender's shard")
     sec, secp = _sections(sections)
-    args = (is_f32, rule, rows, cols, sec.size, secp, tp_dst, tp_src, src_rank, 1 if sends_replicated else 0)
+    args = (is_f32, rule, rows, cols, sec.size, secp, tp_dst, tp_src, src_rank, 1 if sends_replicated else 0,
+            src_groups)
     counts = np.zeros(tp_dst, dtype=np.int64)
     _check(lib.orc_encode_tensor_src(old.ctypes.data, new.ctypes.data, *args, counts.ctypes.data, None, None),
            "encode_tensor_src(count)")

@@ -199,11 +199,46 @@ int orc_encode_tensor(const uint16_t *old_bits, const void *new_data, int new_is
  * holds it (shard map with degree S gives the sender and the index inside its slice) to the
  * destination the shard map with degree D gives.  Entries come out in ascending (r,c).
  */
+/*
+ * Where the sender side keeps row r of a fused tensor when its layout is interleaved by head
+ * group (the usual training-side layout of a fused QKV matrix: for each of G groups its query
+ * rows, then its key rows, then its value rows), and the senders split that layout in S equal
+ * row blocks, i.e. whole groups.  r is the row in the plain [Q;K;V] stacking.  Out: the sender
+ * and the row inside its slice.
+ */
+static int src_row_groups(int64_t R, int n_sec, const int64_t *sec, int S, int G, int64_t r,
+                          int *sender, int64_t *slice_row)
+{
+    if (G < 1 || G % S) return ORC_BAD_SHAPE;
+    int64_t group_rows = 0;
+    for (int j = 0; j < n_sec; ++j) {
+        if (sec[j] % G) return ORC_BAD_SHAPE;
+        group_rows += sec[j] / G;
+    }
+    int64_t first = 0, before = 0;      /* first row of r's section; rows of earlier sections per group */
+    int j = 0;
+    while (r >= first + sec[j]) {
+        first += sec[j];
+        before += sec[j] / G;
+        ++j;
+    }
+    int64_t per = sec[j] / G;           /* rows of this section that belong to one group */
+    int64_t g = (r - first) / per, w = (r - first) % per;
+    int64_t src_row = g * group_rows + before + w;
+    int64_t rows_per_sender = R / S;
+    *sender = (int)(src_row / rows_per_sender);
+    *slice_row = src_row % rows_per_sender;
+    return ORC_OK;
+}
+
+/* src_groups = 0: the sender side stacks sections plainly, like the destination side;
+ * src_groups = G > 0 (fused rows only): the sender side's layout is interleaved by G head groups. */
 int orc_encode_tensor_src(const uint16_t *old_slice, const void *new_slice, int new_is_f32,
                           int rule, int64_t R, int64_t C, int n_sec, const int64_t *sec,
-                          int D, int S, int s, int sends_replicated,
+                          int D, int S, int s, int sends_replicated, int src_groups,
                           int64_t *counts, int32_t *const *idx, uint16_t *const *val)
 {
+    if (src_groups != 0 && rule != ORC_FUSED_ROWS) return ORC_BAD_SHAPE;
     int rc = check_shape(rule, R, C, n_sec, sec, D);
     if (rc) return rc;
     rc = check_shape(rule, R, C, n_sec, sec, S);
@@ -219,7 +254,14 @@ int orc_encode_tensor_src(const uint16_t *old_slice, const void *new_slice, int 
     for (int64_t r = 0; r < R; ++r) {
         for (int64_t c = 0; c < C; ++c) {
             int s_first, n_src; int64_t sl;
-            rc = orc_shard_map(rule, R, C, n_sec, sec, S, r, c, &s_first, &n_src, &sl);
+            if (src_groups) {
+                int64_t row;
+                rc = src_row_groups(R, n_sec, sec, S, src_groups, r, &s_first, &row);
+                n_src = 1;
+                sl = row * C + c;
+            } else {
+                rc = orc_shard_map(rule, R, C, n_sec, sec, S, r, c, &s_first, &n_src, &sl);
+            }
             if (rc) return rc;
             if (s < s_first || s >= s_first + n_src) continue;      /* another sender's element */
             uint16_t nb = new_is_f32 ? orc_rne_bf16(new32[sl]) : new16[sl];

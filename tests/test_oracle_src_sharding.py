@@ -96,3 +96,53 @@ def test_bad_sender_arguments_are_refused():
         oracle.encode_tensor_src(o, o, 8, 4, SPLIT_ROWS, None, 2, 3, 0)          # 8 rows over 3 senders
     with pytest.raises(oracle.OracleError):
         oracle.encode_tensor_src(o[:16], o[:16], 8, 4, SPLIT_ROWS, None, 2, 2, 2)  # rank out of range
+
+
+def interleave_by_groups(x, sec, G):
+    """[Q;K;V] stacking -> per group [q_g; k_g; v_g], with plain numpy slicing."""
+    parts, first = [], []
+    r0 = 0
+    for sj in sec:
+        first.append(r0)
+        r0 += sj
+    for g in range(G):
+        for f, sj in zip(first, sec):
+            per = sj // G
+            parts.append(x[f + g * per:f + (g + 1) * per])
+    return np.concatenate(parts, 0)
+
+
+@pytest.mark.parametrize("sec,C,G", [([32, 8, 8], 5, 8), ([40, 8, 8], 3, 8), ([16, 16, 16], 4, 4), ([24, 24], 2, 4)])
+@pytest.mark.parametrize("S,D", [(1, 1), (1, 4), (2, 4), (4, 2), (4, 4), (2, 1)])
+def test_group_interleaved_sender_layout(sec, C, G, S, D):
+    """The sender side keeps the fused tensor interleaved by head group and splits it in S row
+    blocks (whole groups); built here with numpy slicing of the plain stacking.  The senders'
+    outputs together must be the plain full-tensor encode."""
+    if G % S or any(sj % D for sj in sec):
+        pytest.skip("degree does not divide")
+    R = sum(sec)
+    old, new = synth.pair_bernoulli(R * C, 0.3, seed=R + C + G + 3 * S + D)
+    o, n = bits(old).reshape(R, C), bits(new).reshape(R, C)
+    full = oracle.encode_tensor(o, n, R, C, FUSED_ROWS, sec, D)
+    oi, ni = interleave_by_groups(o, sec, G), interleave_by_groups(n, sec, G)
+    per = R // S
+    per_sender = [oracle.encode_tensor_src(oi[s * per:(s + 1) * per], ni[s * per:(s + 1) * per], R, C, FUSED_ROWS, sec,
+                                           D, S, s, src_groups=G) for s in range(S)]
+    for d in range(D):
+        idx = np.concatenate([ps[d][0] for ps in per_sender])
+        val = np.concatenate([ps[d][1] for ps in per_sender])
+        order = np.argsort(idx, kind="stable")
+        assert np.array_equal(idx[order], full[d][0]) and np.array_equal(val[order], full[d][1]), d
+
+
+def test_group_interleaving_hand_case():
+    """Sections (4, 2, 2), G = 2: plain rows q0 q1 q2 q3 k0 k1 v0 v1 are kept as q0 q1 k0 v0 | q2 q3 k1 v1.
+    One column, everything changes, one destination: sender 1 of 2 holds q2 q3 k1 v1 = plain rows 2 3 5 7."""
+    o = np.zeros(8, dtype=np.uint16)
+    n = np.array([12, 13, 15, 17], dtype=np.uint16)             # the sender's slice, values name plain rows + 10
+    got = oracle.encode_tensor_src(o[:4], n, 8, 1, FUSED_ROWS, [4, 2, 2], 1, 2, 1, src_groups=2)
+    assert got[0][0].tolist() == [2, 3, 5, 7] and got[0][1].tolist() == [12, 13, 15, 17]
+    with pytest.raises(oracle.OracleError):
+        oracle.encode_tensor_src(o[:4], n, 8, 1, FUSED_ROWS, [4, 2, 2], 1, 2, 1, src_groups=3)
+    with pytest.raises(oracle.OracleError):
+        oracle.encode_tensor_src(o, o, 8, 1, SPLIT_ROWS, None, 1, 1, 0, src_groups=2)
