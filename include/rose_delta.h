@@ -68,6 +68,15 @@ typedef struct {
     int32_t rule;                                  /* rose_rule */
     int32_t n_sections;                            /* ROSE_FUSED_ROWS only: 1..ROSE_MAX_SECTIONS */
     int64_t section_rows[ROSE_MAX_SECTIONS];       /* rows of each section, sum = rows */
+    int32_t src_groups;                            /* ROSE_FUSED_ROWS only, sender side: 0 = the sender keeps
+                                                      the sections stacked like the destination; G > 0 = it
+                                                      keeps them interleaved by G head groups (for each group
+                                                      its rows of section 0, then of section 1, ...: the usual
+                                                      training-side layout of a fused QKV matrix) and senders
+                                                      split that layout in tp_src equal row blocks (whole
+                                                      groups).  Every section and tp_src must divide by G
+                                                      resp. into it. */
+    int32_t reserved;                              /* 0 */
 } rose_tensor_desc;
 
 typedef struct rose_plan rose_plan;

@@ -25,7 +25,8 @@ if not os.path.exists(_LIB_PATH):
 
 class TensorDesc(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("rule", ctypes.c_int32),
-                ("n_sections", ctypes.c_int32), ("section_rows", ctypes.c_int64 * ROSE_MAX_SECTIONS)]
+                ("n_sections", ctypes.c_int32), ("section_rows", ctypes.c_int64 * ROSE_MAX_SECTIONS),
+                ("src_groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class CBucket(ctypes.Structure):
@@ -162,6 +163,7 @@ def shard_plan(tensors, tp, tp_src=1, src_rank=0):
         arr[i].n_sections = len(sec)
         for j, s in enumerate(sec):
             arr[i].section_rows[j] = s
+        arr[i].src_groups = int(t.get("src_groups") or 0)
     h = _vp()
     if tp_src == 1 and src_rank == 0:
         _check(_lib.rose_shard_plan_create(arr, len(tensors), tp, ctypes.byref(h)), "shard_plan")

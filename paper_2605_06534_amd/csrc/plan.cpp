@@ -59,6 +59,11 @@ static rose_status check_desc(const rose_tensor_desc &t, int32_t tp) {
     }
     default: return ROSE_ERR_ARG;
     }
+    if (t.src_groups != 0) {
+        if (t.rule != ROSE_FUSED_ROWS || t.src_groups < 0) return ROSE_ERR_ARG;
+        for (int j = 0; j < t.n_sections; ++j)
+            if (t.section_rows[j] % t.src_groups) return ROSE_ERR_SHAPE;
+    }
     // guard rows * cols against int64 overflow, then bound the shard-local size
     if (t.cols != 0 && t.rows > (int64_t)(INT64_MAX / 4) / t.cols) return ROSE_ERR_UNSUPPORTED;
     int64_t local = t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : tp);
@@ -131,6 +136,28 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
                 add(lo - s * (C / S), C / S, lo - d * (C / D), C / D, hi - lo, R * (hi - lo));
             break;
         case ROSE_FUSED_ROWS: {
+            if (t.src_groups > 0) {
+                // The sender keeps the tensor interleaved by head group and holds whole groups
+                // [g0, g1).  In the destination's order (section, then row) the parts it holds of
+                // section j are, group by group, the overlap of the group's rows with shard d's.
+                const int64_t G = t.src_groups;
+                const int64_t g0 = s * (G / S), g1 = (s + 1) * (G / S);
+                int64_t group_rows = 0;
+                for (int j = 0; j < t.n_sections; ++j) group_rows += t.section_rows[j] / G;
+                int64_t before = 0, loc_row = 0;  // rows of earlier sections per group / per shard
+                for (int j = 0; j < t.n_sections; ++j) {
+                    const int64_t per_g = t.section_rows[j] / G, per_d = t.section_rows[j] / D;
+                    for (int64_t g = g0; g < g1; ++g) {
+                        if (overlap(g * per_g, (g + 1) * per_g, d * per_d, (d + 1) * per_d, &lo, &hi)) {
+                            const int64_t src_row = (g - g0) * group_rows + before + (lo - g * per_g);
+                            add(src_row * C, 0, (loc_row + lo - d * per_d) * C, 0, (hi - lo) * C, (hi - lo) * C);
+                        }
+                    }
+                    before += per_g;
+                    loc_row += per_d;
+                }
+                break;
+            }
             int64_t src_row = 0, loc_row = 0;     // first row of section j in the sender's slice / the shard
             for (int j = 0; j < t.n_sections; ++j) {
                 const int64_t per_s = t.section_rows[j] / S, per_d = t.section_rows[j] / D;
@@ -164,6 +191,7 @@ extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensor
     for (int32_t i = 0; i < n_tensors; ++i) {
         rose_status s = check_desc(tensors[i], tp);
         if (s == ROSE_OK) s = check_desc(tensors[i], tp_src);
+        if (s == ROSE_OK && tensors[i].src_groups > 0 && tensors[i].src_groups % tp_src) s = ROSE_ERR_SHAPE;
         if (s != ROSE_OK) return s;
     }
     rose_plan *p = new (std::nothrow) rose_plan;

@@ -94,3 +94,38 @@ def test_full_width_training_to_rollout_8b_layer():
     ts = [t for t in ts if t["name"] not in ("embed", "lm_head")] + [dict(name="embed", rows=151936 // 8, cols=4096,
                                                                        rule=R.SPLIT_ROWS, sections=None)]
     run(ts, 1, 4, 0.02, seed=4)
+
+
+@pytest.mark.parametrize("tp_src,tp", [(1, 4), (4, 4), (8, 4), (2, 8), (4, 1)])
+def test_group_interleaved_qkv_from_the_training_side(tp_src, tp):
+    """Fused QKV kept interleaved by KV-head group on the sender side (built with numpy), plainly
+    stacked on the destination side: GQA shapes with 8 groups of 5 query heads."""
+    from test_oracle_src_sharding import interleave_by_groups
+    print("case: group-interleaved qkv tp_src=%d tp=%d" % (tp_src, tp), flush=True)
+    hd, G, qpg, H = 16, 8, 5, 256
+    sec = [G * qpg * hd, G * hd, G * hd]
+    rows = sum(sec)
+    t = dict(name="qkv", rows=rows, cols=H, rule=R.FUSED_ROWS, sections=sec, src_groups=G)
+    o, n = synth.pair_bernoulli(rows * H, 0.05, seed=tp_src * 100 + tp)
+    o, n = bits(o).reshape(rows, H), bits(n).reshape(rows, H)
+    oi, ni = interleave_by_groups(o, sec, G), interleave_by_groups(n, sec, G)
+    per = rows // tp_src
+    dst = [torch.from_numpy(np_slice(o.ravel(), t, tp, d).view(np.int16).copy()).cuda() for d in range(tp)]
+    for s in range(tp_src):
+        so = torch.from_numpy(np.ascontiguousarray(oi[s * per:(s + 1) * per]).view(np.int16).copy()).cuda()
+        sn = torch.from_numpy(np.ascontiguousarray(ni[s * per:(s + 1) * per]).view(np.int16).copy()).cuda()
+        plan = R.shard_plan([t], tp, tp_src, s)
+        buckets = [R.Bucket(plan.bucket_capacity(d), 1) for d in range(tp)]
+        R.delta_encode(plan, R.ptr_table([so]), R.ptr_table([sn]), R.BF16, buckets, R.workspace(plan))
+        torch.cuda.synchronize()
+        want = oracle.encode_tensor_src(oi[s * per:(s + 1) * per], ni[s * per:(s + 1) * per], rows, H, R.FUSED_ROWS, sec,
+                                        tp, tp_src, s, src_groups=G)
+        for d in range(tp):
+            cnt = R.bucket_check(plan, buckets[d])
+            assert cnt == want[d][0].size, (s, d)
+            assert np.array_equal(buckets[d].idx[:cnt].cpu().numpy(), want[d][0]), (s, d)
+            assert np.array_equal(buckets[d].val[:cnt].cpu().numpy().view(np.uint16), want[d][1]), (s, d)
+            R.delta_apply(plan, d, buckets[d], R.ptr_table([dst[d]]))
+        torch.cuda.synchronize()
+    for d in range(tp):
+        assert np.array_equal(dst[d].cpu().numpy().view(np.uint16), np_slice(n.ravel(), t, tp, d)), d

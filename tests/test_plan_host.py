@@ -86,6 +86,39 @@ def test_sender_side_plan_matches_oracle_maps(tp_src, tp):
         assert [plan.bucket_capacity(d) for d in range(tp)] == cap
 
 
+@pytest.mark.parametrize("sec,C,G", [([32, 8, 8], 5, 8), ([16, 16, 16], 8, 4), ([24, 24], 2, 4)])
+@pytest.mark.parametrize("tp_src,tp", [(1, 1), (1, 4), (2, 4), (4, 2), (4, 4), (2, 1)])
+def test_group_interleaved_sender_plan(sec, C, G, tp_src, tp):
+    """The sender's layout is built with numpy (a tensor holding its own plain index, interleaved by
+    group, cut in row blocks); every element of a slice must go where the oracle's map sends the
+    plain element it is."""
+    import numpy as np
+    from test_oracle_src_sharding import interleave_by_groups
+    if G % tp_src or any(x % tp for x in sec):
+        pytest.skip("degree does not divide")
+    rows = sum(sec)
+    t = dict(name="qkv", rows=rows, cols=C, rule=R.FUSED_ROWS, sections=sec, src_groups=G)
+    plain = np.arange(rows * C, dtype=np.int64).reshape(rows, C)
+    inter = interleave_by_groups(plain, sec, G)
+    per = rows // tp_src
+    for s in range(tp_src):
+        plan = R.shard_plan([t], tp, tp_src, s)
+        sl = inter[s * per:(s + 1) * per].ravel()
+        for g_s, g in enumerate(sl):
+            want = oracle.shard_map(R.FUSED_ROWS, rows, C, sec, tp, int(g) // C, int(g) % C)
+            assert plan.map_index(0, g_s) == want, (s, g_s)
+
+
+def test_group_interleaving_argument_errors():
+    bad = [dict(rows=8, cols=4, rule=R.SPLIT_ROWS, sections=None, src_groups=2),
+           dict(rows=12, cols=4, rule=R.FUSED_ROWS, sections=[8, 2, 2], src_groups=4)]
+    for t in bad:
+        with pytest.raises(R.RoseError):
+            R.shard_plan([t], 1)
+    with pytest.raises(R.RoseError):          # 4 groups cannot be split over 8 senders
+        R.shard_plan([dict(rows=48, cols=4, rule=R.FUSED_ROWS, sections=[16, 16, 16], src_groups=4)], 1, 8, 0)
+
+
 def test_sender_side_plan_argument_errors():
     t = [dict(rows=8, cols=8, rule=R.SPLIT_ROWS, sections=None)]
     for tp_src, rank, status in [(3, 0, binding.ERR_SHAPE), (2, 2, binding.ERR_ARG), (2, -1, binding.ERR_ARG),
