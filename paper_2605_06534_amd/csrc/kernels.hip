@@ -1451,40 +1451,6 @@ __global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char 
     apply_body(b, n_tensors, local_numel, dst_ptrs);
 }
 
-#ifdef ROSE_APPLY_SCATTER
-// plain scatter: a wave takes 256 consecutive entries, lane l the entries l, l + 64, ...
-__global__ __launch_bounds__(kApplyThreads) void apply_scatter_kernel(BucketDev b, int32_t n_tensors,
-                                                                      void *const *dst_ptrs) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int64_t total = b.seg_off[n_tensors];
-    if (total > b.capacity) total = b.capacity;
-    for (int64_t wbase = ((int64_t)blockIdx.x * kApplyWaves + wave) * 256; wbase < total;
-         wbase += (int64_t)gridDim.x * kApplyThreads * 4) {
-        int32_t ix[4];
-        uint16_t vv[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t e = wbase + i * 64 + lane;
-            ix[i] = e < total ? b.idx[e] : 0;
-            vv[i] = e < total ? b.val[e] : (uint16_t)0;
-        }
-        int32_t t = wave_find_segment(b.seg_off, n_tensors, wbase, lane);
-        int64_t seg_end = b.seg_off[t + 1];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t e = wbase + i * 64 + lane;
-            if (e < total) {
-                while (e >= seg_end) {
-                    ++t;
-                    seg_end = b.seg_off[t + 1];
-                }
-                static_cast<uint16_t *>(dst_ptrs[t])[ix[i]] = vv[i];
-            }
-        }
-    }
-}
-#endif
-
 // ---------------------------------------------------------------------------------------------
 // dense copy of one shard: the same tiles as encode, moved instead of compared.
 // ---------------------------------------------------------------------------------------------
@@ -1672,11 +1638,7 @@ int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_num
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = (b.capacity + kApplyThreads - 1) / kApplyThreads;
     int blocks = chunks < 1 ? 1 : (chunks > 256 * 32 ? 256 * 32 : (int)chunks);
-#ifdef ROSE_APPLY_SCATTER
-    hipLaunchKernelGGL(apply_scatter_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, dst_ptrs);
-#else
     hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs);
-#endif
     return (int)hipGetLastError();
 }
 
