@@ -82,8 +82,8 @@ typedef struct {
 typedef struct rose_plan rose_plan;
 
 /*
- * One destination shard's COO data (Sec. 4.2 "shard the COO tensors according to the chosen
- * parallelism strategy").  The struct lives in host memory; all four arrays are device memory.
+ * One destination shard's COO data (Sec. 4.2, sparsity-aware transfer: the COO data is split by the
+ * receiver's parallel layout).  The struct lives in host memory; all four arrays are device memory.
  *   idx      [capacity] int32 local indices, 16-byte aligned
  *   val      [capacity] new 16-bit patterns, 16-byte aligned
  *   seg_off  [n_tensors + 1] int64, 8-byte aligned: after encode, the entries of tensor t are
@@ -192,7 +192,7 @@ rose_status rose_delta_encode_refresh(const rose_plan *plan, void *const *old_pt
                                       void *stream);
 
 /*
- * delta_apply (Sec. 4.2 "each device applies only its local shard", App. F S2D): writes every
+ * delta_apply (Sec. 4.2, sparsity-aware transfer: a receiver applies its own shard only; App. F S2D): writes every
  * entry's value at its local index of shard d's resident copies.
  *   bucket    HOST struct, device arrays as written by rose_delta_encode for shard d
  *   dst_ptrs  DEVICE array of n_tensors device pointers to shard d's local tensors

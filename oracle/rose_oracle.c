@@ -10,8 +10,8 @@
  * What the paper fixes (Sec. 4.2): the delta dW_t = W_t - W_{t-1} is sent in
  * COO form, losslessly, only non-zero elements; the COO data is split by the
  * receiver's parallel layout so that every receiving device applies only its
- * own part onto its resident W_{t-1}; per-parameter shard rules are "sharded
- * dimension -> per-rank slice ranges".
+ * own part onto its resident W_{t-1}; each parameter carries a rule naming
+ * the dimension that is split and the slice of it that each rank holds.
  *
  * Readings taken where the paper is silent (all listed in the design notes):
  *   - weights are 16-bit patterns (bf16); "non-zero delta" means the two bit
