@@ -32,7 +32,7 @@ def build(force=False):
     """Compile the oracle with gcc (plain C, no special flags beyond -O2)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fPIC", "-shared",
-                               "-o", _LIB, _SRC])
+                               "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
@@ -57,6 +57,19 @@ def _load():
         lib.orc_encode_tensor_src.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         lib.orc_apply.restype = i32
         lib.orc_apply.argtypes = [vp, vp, i64, vp, i64]
+        u16 = ctypes.c_uint16
+        lib.orc_bf16_nearest.restype = u16
+        lib.orc_bf16_nearest.argtypes = [ctypes.c_double]
+        lib.orc_bf16_add.restype = u16
+        lib.orc_bf16_add.argtypes = [u16, u16]
+        lib.orc_bf16_sub.restype = u16
+        lib.orc_bf16_sub.argtypes = [u16, u16]
+        lib.orc_arith_payload.restype = i32
+        lib.orc_arith_payload.argtypes = [u16, u16, vp]
+        lib.orc_arith_from_overwrite.restype = i32
+        lib.orc_arith_from_overwrite.argtypes = [vp, vp, i64, vp, i64]
+        lib.orc_apply_arith.restype = i32
+        lib.orc_apply_arith.argtypes = [vp, vp, i64, vp, i64]
         lib.orc_dense_shard.restype = i32
         lib.orc_dense_shard.argtypes = [vp, i32, i64, i64, i32, vp, i32, i32, vp]
         _lib = lib
@@ -198,6 +211,64 @@ def apply_bucket(bucket, dsts):
     for t, dst in enumerate(dsts):
         a, b = int(so[t]), int(so[t + 1])
         apply_segment(bucket["idx"][a:b], bucket["val"][a:b], dst)
+
+
+# ---------------------------------------------------------------------------------------------
+# Arithmetic payload (Sec. 4.2 writes the update as W_t = W_{t-1} + dW_t): an entry carries the
+# bf16-rounded difference where adding it back to the old pattern reproduces the new one, and
+# otherwise the new pattern itself with bit 31 of its index set (int32: a negative index).
+# ---------------------------------------------------------------------------------------------
+ESCAPE = np.int32(-2**31)
+
+
+def bf16_nearest(x):
+    """bf16 pattern nearest to the double x (ties to even)."""
+    return int(_load().orc_bf16_nearest(float(x)))
+
+
+def bf16_add(a, b):
+    return int(_load().orc_bf16_add(int(a), int(b)))
+
+
+def bf16_sub(a, b):
+    return int(_load().orc_bf16_sub(int(a), int(b)))
+
+
+def arith_payload(old_bits, new_bits):
+    """(escape, val) of one entry."""
+    v = ctypes.c_uint16(0)
+    esc = _load().orc_arith_payload(int(old_bits), int(new_bits), ctypes.addressof(v))
+    return bool(esc), int(v.value)
+
+
+def arith_bucket(bucket, old_locals):
+    """The bucket with arithmetic payloads; ``old_locals[t]`` is the receiver's resident copy
+    (uint16, flat) of tensor t, the value it will add to.  Returns a new bucket."""
+    idx = np.array(bucket["idx"], dtype=np.int32, copy=True)
+    val = np.array(bucket["val"], dtype=np.uint16, copy=True)
+    so = bucket["seg_off"]
+    for t, old in enumerate(old_locals):
+        a, b = int(so[t]), int(so[t + 1])
+        old = np.ascontiguousarray(old).view(np.uint16).ravel()
+        si, sv = idx[a:b], val[a:b]          # contiguous views: converted in place
+        _check(_load().orc_arith_from_overwrite(si.ctypes.data, sv.ctypes.data, b - a, old.ctypes.data, old.size),
+               "arith_from_overwrite")
+    return {"idx": idx, "val": val, "seg_off": np.array(so, dtype=np.int64, copy=True)}
+
+
+def apply_segment_arith(idx, val, dst):
+    assert dst.dtype == np.uint16 and dst.flags["C_CONTIGUOUS"]
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=np.uint16)
+    _check(_load().orc_apply_arith(idx.ctypes.data, val.ctypes.data, idx.size, dst.ctypes.data, dst.size),
+           "apply_arith")
+
+
+def apply_bucket_arith(bucket, dsts):
+    so = bucket["seg_off"]
+    for t, dst in enumerate(dsts):
+        a, b = int(so[t]), int(so[t + 1])
+        apply_segment_arith(bucket["idx"][a:b], bucket["val"][a:b], dst)
 
 
 def dense_shard(full, rows, cols, rule, sections, tp, d):

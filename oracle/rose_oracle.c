@@ -17,8 +17,10 @@
  *   - weights are 16-bit patterns (bf16); "non-zero delta" means the two bit
  *     patterns differ (so +0 -> -0 is a change, an identical NaN is not);
  *   - the payload of an entry is the NEW 16-bit pattern, applying = overwrite
- *     (an arithmetic bf16 difference is not exact in general, so it could not
- *     be lossless);
+ *     (an arithmetic bf16 difference is not exact in general, so alone it
+ *     could not be lossless); the arithmetic variant further down carries the
+ *     rounded difference where that is exact and escapes to the pattern
+ *     where it is not;
  *   - an entry's coordinate is one linear index, local to the destination
  *     shard's copy of that tensor (int32);
  *   - entries of one (tensor, shard) segment are in ascending local index;
@@ -293,6 +295,108 @@ int orc_apply(const int32_t *idx, const uint16_t *val, int64_t count,
     for (int64_t k = 0; k < count; ++k) {
         if (idx[k] < 0 || (int64_t)idx[k] >= dst_numel) return ORC_RANGE;
         dst[idx[k]] = val[k];
+    }
+    return ORC_OK;
+}
+
+/*
+ * Arithmetic payload (Sec. 4.2 states the update as W_t = W_{t-1} + dW_t; this is the variant
+ * that takes it literally).  bf16 arithmetic rounds, so an entry carries the rounded difference
+ * only where adding it back reproduces the new pattern; every other entry falls back to carrying
+ * the new pattern itself and says so in the sign bit of its index.  With that escape the variant
+ * stays lossless for every pair of bit patterns.  (A reading: the paper gives no element format.)
+ *
+ * The value of a bf16 pattern as a double (exact: a double holds every bf16 value).
+ */
+#include <math.h>
+#include <string.h>
+
+static double bf16_value(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/*
+ * The bf16 pattern nearest to x, ties to the even significand, by the definition of the format:
+ * 8 significant bits, exponents 2^-126 .. 2^127, below that fixed steps of 2^-133, beyond the
+ * largest finite value (after rounding) infinity.  NaN gives the default NaN 0x7FC0.
+ */
+uint16_t orc_bf16_nearest(double x)
+{
+    if (isnan(x)) return 0x7FC0u;
+    uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    double a = fabs(x);
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                  /* a = m * 2^e, 0.5 <= m < 1  ->  leading bit 2^(e-1) */
+    int lead = e - 1;
+    if (lead < -126) lead = -126;        /* subnormal range: the step stays 2^-133            */
+    double step = ldexp(1.0, lead - 7);  /* spacing of bf16 values in this binade             */
+    double n = rint(a / step);           /* a power-of-two scaling is exact; rint: ties to even
+                                            (the default rounding mode is never changed here)  */
+    double r = n * step;                 /* exact: at most 9 significant bits                  */
+    if (r >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7F80u);
+    float f = (float)r;                  /* exact                                              */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(sign | (uint16_t)(u >> 16));
+}
+
+/* correctly rounded bf16 sum and difference of two bf16 patterns.  The double result is exact
+ * unless the operands' exponents are more than 40 binades apart, and then it differs from the
+ * larger operand by far less than a quarter of a bf16 step, so rounding it again cannot land on
+ * the other side of a tie. */
+uint16_t orc_bf16_add(uint16_t a, uint16_t b) { return orc_bf16_nearest(bf16_value(a) + bf16_value(b)); }
+uint16_t orc_bf16_sub(uint16_t a, uint16_t b) { return orc_bf16_nearest(bf16_value(a) - bf16_value(b)); }
+
+/*
+ * One entry: *val = the rounded difference and 0 is returned if the difference is a number and
+ * old + difference rounds back to exactly the new pattern; otherwise *val = the new pattern and
+ * 1 is returned (escape).
+ */
+int orc_arith_payload(uint16_t old_bits, uint16_t new_bits, uint16_t *val)
+{
+    uint16_t d = orc_bf16_sub(new_bits, old_bits);
+    int d_is_nan = (d & 0x7FFFu) > 0x7F80u;
+    if (!d_is_nan && orc_bf16_add(old_bits, d) == new_bits) {
+        *val = d;
+        return 0;
+    }
+    *val = new_bits;
+    return 1;
+}
+
+/*
+ * Turn the entries of one (tensor, shard) segment from "new pattern" payloads into arithmetic
+ * ones, in place.  old_local is the receiver's resident copy W_{t-1} of that shard (the value the
+ * receiver will add to).  An escaped entry gets bit 31 of its index set.
+ */
+int orc_arith_from_overwrite(int32_t *idx, uint16_t *val, int64_t count,
+                             const uint16_t *old_local, int64_t numel)
+{
+    for (int64_t k = 0; k < count; ++k) {
+        if (idx[k] < 0 || (int64_t)idx[k] >= numel) return ORC_RANGE;
+        uint16_t v;
+        int esc = orc_arith_payload(old_local[idx[k]], val[k], &v);
+        val[k] = v;
+        if (esc) idx[k] = (int32_t)((uint32_t)idx[k] | 0x80000000u);
+    }
+    return ORC_OK;
+}
+
+/* Sparse-to-dense for arithmetic entries: add (rounded), or overwrite where the entry says so. */
+int orc_apply_arith(const int32_t *idx, const uint16_t *val, int64_t count,
+                    uint16_t *dst, int64_t dst_numel)
+{
+    for (int64_t k = 0; k < count; ++k) {
+        int64_t i = (int64_t)((uint32_t)idx[k] & 0x7FFFFFFFu);
+        if (i >= dst_numel) return ORC_RANGE;
+        if (idx[k] < 0) dst[i] = val[k];
+        else dst[i] = orc_bf16_add(dst[i], val[k]);
     }
     return ORC_OK;
 }
