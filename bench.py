@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--tp-src", type=int, default=1,
                     help="sender-side sharding: time the sender that holds shard --src-rank of this many")
     ap.add_argument("--src-rank", type=int, default=0)
+    ap.add_argument("--payload", choices=("new", "arith"), default="new",
+                    help="entry payload: the new pattern (default) or the arithmetic difference with escapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=float, default=4.0e9)
     ap.add_argument("--graph", action="store_true",
@@ -117,14 +119,22 @@ def main():
         shard_tabs.append(tab)
     torch.cuda.synchronize()
 
+    arith = args.payload == "arith"
+
     def step(ev=None):
         if ev:
             ev[0].record()
-        R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
+        if arith:
+            R.delta_encode_ex(plan, old_tab, new_tab, new_dtype, R.ENCODE_ARITH, buckets, ws)
+        else:
+            R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
         if ev:
             ev[1].record()
         for d in range(tp):
-            R.delta_apply(plan, d, buckets[d], shard_tabs[d])
+            if arith:
+                R.delta_apply_ex(plan, d, buckets[d], R.PAYLOAD_ARITH, shard_tabs[d])
+            else:
+                R.delta_apply(plan, d, buckets[d], shard_tabs[d])
         if ev:
             ev[2].record()
 
@@ -134,6 +144,13 @@ def main():
     nnz = [R.bucket_check(plan, buckets[d]) for d in range(tp)]    # raises if a bucket overflowed
     nnz_total = sum(nnz)
 
+    if arith:
+        # an arithmetic bucket may be applied once only: start the receivers from W_{t-1} again and
+        # take one step before checking (the timed steps below keep adding; their values are not used)
+        for d in range(tp):
+            R.dense_copy(plan, d, old_tab, R.BF16, shard_tabs[d])
+        step()
+        torch.cuda.synchronize()
     # the receiver now holds W_t: check one shard tensor per rule class against a dense copy
     chk = [x.clone() for x in shards[tp - 1]]
     R.dense_copy(plan, tp - 1, new_tab, new_dtype, R.ptr_table(chk))
@@ -250,7 +267,7 @@ def main():
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": args.workload, "elements": n_elems, "tensors": len(tensors), "tp": tp,
                    "recipe": recipe, "density": p, "nnz": nnz_total, "seed": args.seed,
-                   "tp_src": args.tp_src, "src_rank": args.src_rank, "hip_graph": bool(args.graph),
+                   "tp_src": args.tp_src, "src_rank": args.src_rank, "hip_graph": bool(args.graph), "payload": args.payload,
                    "new_dtype": "fp32->bf16 RNE" if new_dtype == R.FP32_RNE else "bf16"},
         "roofline": {"bound": "hbm", "kernel": "encode_kernel",
                      "achieved": round(enc_bytes / 1e9 / (t_enc / 1e3), 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -192,12 +192,44 @@ rose_status rose_delta_encode_refresh(const rose_plan *plan, void *const *old_pt
                                       void *stream);
 
 /*
+ * Arithmetic payload (Sec. 4.2 states the update as W_t = W_{t-1} + dW_t; a variant that takes this
+ * literally.  The paper fixes no element format: the rule below is this library's).
+ * An entry of a bucket written with ROSE_ENCODE_ARITH carries val = bf16(new - old), rounded to
+ * nearest even, if that difference is a number and bf16(old + val) is exactly the new pattern; the
+ * receiver then ADDS val to its resident value (same rounding).  Where that does not hold (large
+ * jumps, a change of a zero's sign, infinities and NaNs) the entry carries the new pattern instead
+ * and bit 31 of its index is set (the index is negative); the receiver overwrites.  Index order,
+ * counts and seg_off are the same as for the default payload, so buckets have the same size.
+ * With the escape the variant is lossless for all patterns, PROVIDED the receiver's copy holds
+ * exactly the sender's old weights: unlike the default payload, applying a bucket twice, or onto
+ * another state, gives wrong weights.  Subnormal values are kept, not flushed.
+ *
+ * rose_delta_encode_ex   rose_delta_encode with flags: ROSE_ENCODE_REFRESH as
+ *                        rose_delta_encode_refresh (old tensors are written), ROSE_ENCODE_ARITH
+ *                        arithmetic payloads; flags = 0 is rose_delta_encode.  Unknown bits:
+ *                        ROSE_ERR_ARG.
+ * rose_delta_apply_ex    rose_delta_apply for a bucket of the given payload kind.
+ * rose_bucket_pack_ex    rose_bucket_pack that records the payload kind in the object's header
+ *                        (u32 at byte 32); rose_object_apply reads it there.
+ */
+#define ROSE_ENCODE_REFRESH 1u
+#define ROSE_ENCODE_ARITH 2u
+#define ROSE_PAYLOAD_NEW 0
+#define ROSE_PAYLOAD_ARITH 1
+rose_status rose_delta_encode_ex(const rose_plan *plan, void *const *old_ptrs, const void *const *new_ptrs,
+                                 int32_t new_dtype, uint32_t flags, const rose_bucket *buckets,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+rose_status rose_delta_apply_ex(const rose_plan *plan, int32_t d, const rose_bucket *bucket, int32_t payload,
+                                void *const *dst_ptrs, void *stream);
+
+/*
  * delta_apply (Sec. 4.2, sparsity-aware transfer: a receiver applies its own shard only; App. F S2D): writes every
  * entry's value at its local index of shard d's resident copies.
  *   bucket    HOST struct, device arrays as written by rose_delta_encode for shard d
  *   dst_ptrs  DEVICE array of n_tensors device pointers to shard d's local tensors
  *             (rose_plan_local_numel elements each, 2-byte aligned at least)
- * Entries at positions >= capacity (an overflowed bucket) are not applied.
+ * Entries at positions >= capacity (an overflowed bucket) are not applied, nor are entries whose
+ * index lies outside their tensor.
  * The kernel reads and rewrites whole 64-byte pieces of a destination tensor around the entries
  * it applies (never a byte outside the tensor): nothing else may write the destination tensors
  * while the call runs.  The first device call on a plan (encode, apply or dense copy) uploads the
@@ -229,7 +261,7 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
  * own format; all of it device memory, 16-byte aligned):
  *     0  u32 magic ROSE_OBJECT_MAGIC, u32 version 1, i32 shard, i32 T
  *    16  i64 first_entry (position of the object's first entry in the shard's stream), i64 n
- *    32  zero up to 64
+ *    32  u32 payload kind (0 new patterns, 1 arithmetic payloads), then zero up to 64
  *    64  i64 seg_off[T + 1]: the entries of tensor t are [seg_off[t], seg_off[t+1]) of THIS object
  *     A  i32 idx[n], A = 64 + 8 (T + 1) rounded up to 16
  *     B  u16 val[n], B = A + 4 n rounded up to 16; size = B + 2 n rounded up to 16 (slack is zero)
@@ -251,6 +283,9 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
 rose_status rose_object_bytes(const rose_plan *plan, int64_t n_entries, size_t *bytes);
 rose_status rose_bucket_pack(const rose_plan *plan, int32_t d, const rose_bucket *bucket, int64_t first_entry,
                              int64_t n_entries, void *object, size_t object_bytes, void *stream);
+rose_status rose_bucket_pack_ex(const rose_plan *plan, int32_t d, const rose_bucket *bucket, int32_t payload,
+                                int64_t first_entry, int64_t n_entries, void *object, size_t object_bytes,
+                                void *stream);
 rose_status rose_object_apply(const rose_plan *plan, const void *object, size_t object_bytes,
                               void *const *dst_ptrs, void *stream);
 rose_status rose_object_check(const rose_plan *plan, const void *object, size_t object_bytes, void *stream,

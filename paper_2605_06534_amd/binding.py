@@ -51,11 +51,14 @@ _SIGS = {
     "rose_plan_n_tiles": (_i32, [_vp, _P(_i64)]),
     "rose_delta_encode": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
     "rose_delta_encode_refresh": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
+    "rose_delta_encode_ex": (_i32, [_vp, _vp, _vp, _i32, ctypes.c_uint32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
     "rose_delta_apply": (_i32, [_vp, _i32, _P(CBucket), _vp, _vp]),
+    "rose_delta_apply_ex": (_i32, [_vp, _i32, _P(CBucket), _i32, _vp, _vp]),
     "rose_dense_copy": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp]),
     "rose_bucket_check": (_i32, [_vp, _P(CBucket), _vp, _P(_i64)]),
     "rose_object_bytes": (_i32, [_vp, _i64, _P(ctypes.c_size_t)]),
     "rose_bucket_pack": (_i32, [_vp, _i32, _P(CBucket), _i64, _i64, _vp, ctypes.c_size_t, _vp]),
+    "rose_bucket_pack_ex": (_i32, [_vp, _i32, _P(CBucket), _i32, _i64, _i64, _vp, ctypes.c_size_t, _vp]),
     "rose_object_apply": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
     "rose_object_check": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _P(_i32), _P(_i64), _P(_i64)]),
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
@@ -207,6 +210,30 @@ def delta_encode_refresh(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=
     _check(_lib.rose_delta_encode_refresh(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, cb,
                                           ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
            "delta_encode_refresh")
+
+
+ENCODE_REFRESH, ENCODE_ARITH = 1, 2
+PAYLOAD_NEW, PAYLOAD_ARITH = 0, 1
+
+
+def delta_encode_ex(plan, old_tab, new_tab, new_dtype, flags, buckets, ws, stream=None):
+    """delta_encode with flags: ENCODE_REFRESH (old tensors are written), ENCODE_ARITH (arithmetic payloads)."""
+    cb = (CBucket * plan.tp)(*[b.c() for b in buckets])
+    _check(_lib.rose_delta_encode_ex(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, flags, cb,
+                                     ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
+           "delta_encode_ex")
+
+
+def delta_apply_ex(plan, d, bucket, payload, dst_tab, stream=None):
+    cb = bucket.c()
+    _check(_lib.rose_delta_apply_ex(plan._h, d, ctypes.byref(cb), payload, dst_tab.data_ptr(), _stream(stream)),
+           "delta_apply_ex")
+
+
+def bucket_pack_ex(plan, d, bucket, payload, first_entry, n_entries, obj, stream=None):
+    cb = bucket.c()
+    _check(_lib.rose_bucket_pack_ex(plan._h, d, ctypes.byref(cb), payload, first_entry, n_entries, obj.data_ptr(),
+                                    obj.numel() * obj.element_size(), _stream(stream)), "bucket_pack_ex")
 
 
 def delta_apply(plan, d, bucket, dst_tab, stream=None):

@@ -93,7 +93,7 @@ extern "C" void rose_shard_plan_destroy(rose_plan *p) {
 
 static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs, const void *const *new_ptrs,
                                  int32_t new_dtype, const rose_bucket *buckets, void *workspace,
-                                 size_t workspace_bytes, bool refresh, void *stream) {
+                                 size_t workspace_bytes, bool refresh, bool arith, void *stream) {
     if (!p || !old_ptrs || !new_ptrs || !buckets || !workspace) return ROSE_ERR_ARG;
     if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
     size_t need = 0;
@@ -126,15 +126,16 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     a.tp = p->tp;
     a.n_tensors = p->n_tensors;
     rose::RefreshArgs r{p->d_repl_list, p->d_repl_numel, p->n_repl};
-    return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, refresh ? &r : nullptr, stream) == 0 ? ROSE_OK
-                                                                                                  : ROSE_ERR_HIP;
+    return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, refresh ? &r : nullptr, arith ? 1 : 0, stream) == 0
+               ? ROSE_OK
+               : ROSE_ERR_HIP;
 }
 
 extern "C" rose_status rose_delta_encode(const rose_plan *p, const void *const *old_ptrs,
                                          const void *const *new_ptrs, int32_t new_dtype,
                                          const rose_bucket *buckets, void *workspace,
                                          size_t workspace_bytes, void *stream) {
-    return encode_common(p, old_ptrs, new_ptrs, new_dtype, buckets, workspace, workspace_bytes, false, stream);
+    return encode_common(p, old_ptrs, new_ptrs, new_dtype, buckets, workspace, workspace_bytes, false, false, stream);
 }
 
 extern "C" rose_status rose_delta_encode_refresh(const rose_plan *p, void *const *old_ptrs,
@@ -142,12 +143,21 @@ extern "C" rose_status rose_delta_encode_refresh(const rose_plan *p, void *const
                                                  const rose_bucket *buckets, void *workspace,
                                                  size_t workspace_bytes, void *stream) {
     return encode_common(p, const_cast<const void *const *>(old_ptrs), new_ptrs, new_dtype, buckets, workspace,
-                         workspace_bytes, true, stream);
+                         workspace_bytes, true, false, stream);
 }
 
-extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const rose_bucket *bucket,
-                                        void *const *dst_ptrs, void *stream) {
+extern "C" rose_status rose_delta_encode_ex(const rose_plan *p, void *const *old_ptrs, const void *const *new_ptrs,
+                                            int32_t new_dtype, uint32_t flags, const rose_bucket *buckets,
+                                            void *workspace, size_t workspace_bytes, void *stream) {
+    if (flags & ~(uint32_t)(ROSE_ENCODE_REFRESH | ROSE_ENCODE_ARITH)) return ROSE_ERR_ARG;
+    return encode_common(p, const_cast<const void *const *>(old_ptrs), new_ptrs, new_dtype, buckets, workspace,
+                         workspace_bytes, (flags & ROSE_ENCODE_REFRESH) != 0, (flags & ROSE_ENCODE_ARITH) != 0, stream);
+}
+
+static rose_status apply_common(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,
+                                void *const *dst_ptrs, void *stream) {
     if (!p || !bucket || !dst_ptrs || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
+    if (payload != ROSE_PAYLOAD_NEW && payload != ROSE_PAYLOAD_ARITH) return ROSE_ERR_ARG;
     rose_status s = check_bucket(*bucket);
     if (s != ROSE_OK) return s;
     if (!aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
@@ -156,7 +166,17 @@ extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const ros
     const int32_t *tile_piece = nullptr, *local_numel = nullptr;
     s = device_tables(p, &pieces, &tile_piece, &local_numel);
     if (s != ROSE_OK) return s;
-    return rose::launch_apply(b, p->n_tensors, local_numel, dst_ptrs, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+    return rose::launch_apply(b, p->n_tensors, local_numel, dst_ptrs, payload, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const rose_bucket *bucket,
+                                        void *const *dst_ptrs, void *stream) {
+    return apply_common(p, d, bucket, ROSE_PAYLOAD_NEW, dst_ptrs, stream);
+}
+
+extern "C" rose_status rose_delta_apply_ex(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,
+                                           void *const *dst_ptrs, void *stream) {
+    return apply_common(p, d, bucket, payload, dst_ptrs, stream);
 }
 
 extern "C" rose_status rose_dense_copy(const rose_plan *p, int32_t d, const void *const *new_ptrs,
@@ -213,16 +233,30 @@ extern "C" rose_status rose_object_bytes(const rose_plan *p, int64_t n_entries, 
     return ROSE_OK;
 }
 
-extern "C" rose_status rose_bucket_pack(const rose_plan *p, int32_t d, const rose_bucket *bucket, int64_t first_entry,
-                                        int64_t n_entries, void *object, size_t object_bytes, void *stream) {
+static rose_status pack_common(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,
+                               int64_t first_entry, int64_t n_entries, void *object, size_t object_bytes,
+                               void *stream) {
     if (!p || !bucket || !object || d < 0 || d >= p->tp || first_entry < 0 || n_entries < 0) return ROSE_ERR_ARG;
+    if (payload != ROSE_PAYLOAD_NEW && payload != ROSE_PAYLOAD_ARITH) return ROSE_ERR_ARG;
     rose_status s = check_bucket(*bucket);
     if (s != ROSE_OK) return s;
     if (!aligned(object, 16)) return ROSE_ERR_ALIGN;
     if (first_entry + n_entries > bucket->capacity) return ROSE_ERR_ARG;
     if (object_bytes < rose::object_bytes_for(p->n_tensors, n_entries)) return ROSE_ERR_CAPACITY;
     rose::BucketDev b{bucket->idx, bucket->val, bucket->capacity, bucket->seg_off};
-    return rose::launch_pack(b, d, p->n_tensors, first_entry, n_entries, object, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+    return rose::launch_pack(b, d, p->n_tensors, first_entry, n_entries, payload, object, stream) == 0 ? ROSE_OK
+                                                                                                       : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_bucket_pack(const rose_plan *p, int32_t d, const rose_bucket *bucket, int64_t first_entry,
+                                        int64_t n_entries, void *object, size_t object_bytes, void *stream) {
+    return pack_common(p, d, bucket, ROSE_PAYLOAD_NEW, first_entry, n_entries, object, object_bytes, stream);
+}
+
+extern "C" rose_status rose_bucket_pack_ex(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,
+                                           int64_t first_entry, int64_t n_entries, void *object, size_t object_bytes,
+                                           void *stream) {
+    return pack_common(p, d, bucket, payload, first_entry, n_entries, object, object_bytes, stream);
 }
 
 extern "C" rose_status rose_object_apply(const rose_plan *p, const void *object, size_t object_bytes,

@@ -50,6 +50,61 @@ __device__ __forceinline__ uint32_t pick16(uint4 v, uint32_t e) {
     return (e & 1u) ? (a >> 16) : (a & 0xFFFFu);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Arithmetic payload (Sec. 4.2 writes the update as W_t = W_{t-1} + dW_t).  An entry carries
+// d = bf16(new - old) if d is a number and bf16(old + d) is exactly the new pattern; otherwise it
+// carries the new pattern and bit 31 of its index says so (escape).  Sums and differences of two
+// bf16 values are formed in fp32 and rounded to nearest even: the fp32 result is exact unless the
+// operands lie more than 16 binades apart, and then it sits so close to the larger operand that
+// the second rounding cannot cross a tie, so the result is the correctly rounded bf16 one.
+// Subnormals are kept (the kernels are built with IEEE denormal handling for fp32).
+// ---------------------------------------------------------------------------------------------
+#ifndef ROSE_ARITH_HWCVT
+#define ROSE_ARITH_HWCVT 1     // 1: round with the packed fp32 -> bf16 conversion instruction (checked against
+                               // the integer rounding below and the CPU reference on all 2^32 pattern pairs;
+                               // 7B workload at 5 %: encode 5.60 ms instead of 6.14 ms)
+#endif
+// the two fp32 values rounded to bf16 (nearest even), packed: lo in bits 0..15, hi in 16..31.
+// A NaN stays a NaN (its low 16 bits are zero here, so the rounding add cannot carry out of them).
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
+#if ROSE_ARITH_HWCVT
+    uint32_t r;
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    return r;
+#else
+    const uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+    const uint32_t ra = a + 0x7FFFu + ((a >> 16) & 1u), rb = b + 0x7FFFu + ((b >> 16) & 1u);
+    return (ra >> 16) | (rb & 0xFFFF0000u);
+#endif
+}
+// payloads of the two elements of a dword; *b01 gets 1 in bit 0 / bit 16 for an escaped element
+__device__ __forceinline__ uint32_t arith_pair(uint32_t o, uint32_t n, uint32_t *b01) {
+    const float ol = __uint_as_float(o << 16), oh = __uint_as_float(o & 0xFFFF0000u);
+    const float nl = __uint_as_float(n << 16), nh = __uint_as_float(n & 0xFFFF0000u);
+    const uint32_t d = pack_bf16_pair(nl - ol, nh - oh);
+    const uint32_t back = pack_bf16_pair(ol + __uint_as_float(d << 16), oh + __uint_as_float(d & 0xFFFF0000u));
+    // a half of `nan` is non-zero where d is a NaN: magnitude above the pattern of infinity
+    uint32_t mx;
+    asm("v_pk_max_u16 %0, %1, %2" : "=v"(mx) : "v"(d & 0x7FFF7FFFu), "v"(0x7F807F80u));
+    const uint32_t bad = (back ^ n) | (mx ^ 0x7F807F80u);
+    const uint32_t b = nz16_pair(bad);
+    *b01 = b;
+    const uint32_t take_new = b * 0xFFFFu;              // 0xFFFF in the halves that escape
+    return (n & take_new) | (d & ~take_new);
+}
+// the same for a vector of eight; esc8 bit e = element e escapes
+__device__ __forceinline__ uint4 arith_vec(uint4 o, uint4 n, uint32_t *esc8) {
+    uint32_t b0, b1, b2, b3;
+    uint4 p;
+    p.x = arith_pair(o.x, n.x, &b0);
+    p.y = arith_pair(o.y, n.y, &b1);
+    p.z = arith_pair(o.z, n.z, &b2);
+    p.w = arith_pair(o.w, n.w, &b3);
+    const uint32_t t = b0 | (b1 << 2) | (b2 << 4) | (b3 << 6);
+    *esc8 = (t | (t >> 15)) & 0xFFu;
+    return p;
+}
+
 // inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS traffic): shifts by
 // 1, 2, 4, 8 inside each row of 16 lanes, then the row totals are broadcast into the following
 // rows (lane 15 of a row into the next row, lane 31 into the upper half).  A lane without a
@@ -116,6 +171,7 @@ __device__ __forceinline__ uint64_t cload64(const void *p) {
 }
 __device__ __forceinline__ Piece load_piece(const Piece *p) {
     static_assert(sizeof(Piece) == 7 * 8, "piece is read as seven 64-bit words");
+    static_assert(kTile <= (1 << 13), "a ring entry keeps the offset inside a tile in 13 bits");
     uint64_t w[7];
 #pragma unroll
     for (int i = 0; i < 7; ++i) w[i] = cload64(reinterpret_cast<const uint64_t *>(p) + i);
@@ -285,32 +341,35 @@ __global__ void finalize_kernel(EncodeArgs a) {
 //                   lane 0 of the reserved register.  Nothing waits.
 //   ticket_take:    waits for every outstanding vector memory operation of the wave, then reads
 //                   the reserved register.
-// The bf16 kernel has 128 registers per lane (4 waves per SIMD), the fp32-master kernel 168 (3).
-#define ROSE_TICKET_VGPR_BF16 "v127"
-#define ROSE_TICKET_VGPR_F32 "v167"
-constexpr int kNumVgprBf16 = 126, kNumVgprF32 = 166;     // what the compiler may use
-template <int NEW_F32>
+// A kernel with 4 waves per SIMD has 128 registers per lane (CLASS = 0), one with 3 has 168 (1),
+// one with 2 has 256 (2).
+#define ROSE_TICKET_VGPR_0 "v127"
+#define ROSE_TICKET_VGPR_1 "v167"
+#define ROSE_TICKET_VGPR_2 "v255"
+constexpr int kNumVgpr0 = 126, kNumVgpr1 = 166, kNumVgpr2 = 254;     // what the compiler may use
+#define ROSE_TICKET_REQUEST(REG)                                                                              \
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add " REG                         \
+                 ", %1, %2, %3 sc0\n\ts_mov_b64 exec, %0"                                                     \
+                 : "=&s"(saved) : "v"(zero), "v"(one), "s"(counter) : "memory", REG)
+#define ROSE_TICKET_TAKE(REG) asm volatile("s_waitcnt vmcnt(0)\n\tv_mov_b32 %0, " REG : "=v"(t) : : "memory")
+template <int CLASS>
 __device__ __forceinline__ void ticket_request(unsigned int *counter) {
     unsigned long long saved;
     const unsigned int zero = 0, one = 1;
-    if constexpr (NEW_F32)
-        asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add " ROSE_TICKET_VGPR_F32
-                     ", %1, %2, %3 sc0\n\ts_mov_b64 exec, %0"
-                     : "=&s"(saved) : "v"(zero), "v"(one), "s"(counter) : "memory", ROSE_TICKET_VGPR_F32);
-    else
-        asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add " ROSE_TICKET_VGPR_BF16
-                     ", %1, %2, %3 sc0\n\ts_mov_b64 exec, %0"
-                     : "=&s"(saved) : "v"(zero), "v"(one), "s"(counter) : "memory", ROSE_TICKET_VGPR_BF16);
+    if constexpr (CLASS == 2) ROSE_TICKET_REQUEST(ROSE_TICKET_VGPR_2);
+    else if constexpr (CLASS == 1) ROSE_TICKET_REQUEST(ROSE_TICKET_VGPR_1);
+    else ROSE_TICKET_REQUEST(ROSE_TICKET_VGPR_0);
 }
-template <int NEW_F32>
+template <int CLASS>
 __device__ __forceinline__ unsigned int ticket_take() {
     unsigned int t;
-    if constexpr (NEW_F32)
-        asm volatile("s_waitcnt vmcnt(0)\n\tv_mov_b32 %0, " ROSE_TICKET_VGPR_F32 : "=v"(t) : : "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(0)\n\tv_mov_b32 %0, " ROSE_TICKET_VGPR_BF16 : "=v"(t) : : "memory");
+    if constexpr (CLASS == 2) ROSE_TICKET_TAKE(ROSE_TICKET_VGPR_2);
+    else if constexpr (CLASS == 1) ROSE_TICKET_TAKE(ROSE_TICKET_VGPR_1);
+    else ROSE_TICKET_TAKE(ROSE_TICKET_VGPR_0);
     return t;
 }
+#undef ROSE_TICKET_REQUEST
+#undef ROSE_TICKET_TAKE
 
 __device__ __forceinline__ bool has_prefix(u64 word) { return (word >> kStatusShift) == kStatusPrefix; }
 
@@ -589,9 +648,12 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
     }
 }
 
-template <int NEW_F32, int REFRESH>
+template <int NEW_F32, int REFRESH, int ARITH>
 __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
-    __shared__ uint32_t s_ring[kRing];      // an entry: offset inside its tile << 16 | value
+    // register class, see ticket_request
+    constexpr int WIDE = (NEW_F32 && REFRESH && ARITH) ? 2 : (NEW_F32 || (REFRESH && ARITH)) ? 1 : 0;
+    __shared__ uint32_t s_ring[kRing];      // an entry: offset inside its tile (13 bits) << 16 | value;
+                                            // bit 31: the entry escapes (arithmetic payload only)
     __shared__ uint32_t s_wave_total[2][kWaves];
     __shared__ u64 s_excl[2][kQueue];       // prefixes of the tiles an iteration copies out, oldest first
     __shared__ u64 s_excl_sync[kQueue];     // the same for a blocking drain
@@ -678,11 +740,12 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                     const u64 pos = excl + k;
                     if (pos < (u64)b.capacity) {
                         const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
-                        uint32_t local = base + (entry >> 16);
+                        uint32_t local = base + (ARITH ? (entry >> 16) & (uint32_t)(kTile - 1) : entry >> 16);
                         if (piece >= 0) {              // base is the tile's first element number here
                             const uint32_t q = __umulhi(local, l_magic) >> l_shift;
                             local = l_base + q * l_stride + (local - q * l_run);
                         }
+                        if constexpr (ARITH) local |= entry & 0x80000000u;
 #if ROSE_NT_STORES
                         __builtin_nontemporal_store((int32_t)local, b.idx + pos);
                         __builtin_nontemporal_store((uint16_t)entry, b.val + pos);
@@ -761,8 +824,8 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     // its way, if any, else asks for one.
     auto settle_ticket = [&]() {
         if (threadIdx.x == 0) {
-            if (!ticket_out) ticket_request<NEW_F32>(a.ticket);
-            s_ticket_sync = (int32_t)ticket_take<NEW_F32>();
+            if (!ticket_out) ticket_request<WIDE>(a.ticket);
+            s_ticket_sync = (int32_t)ticket_take<WIDE>();
         }
         ticket_out = false;
         __syncthreads();
@@ -843,7 +906,9 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         cur = loaded ? nxt : start_tile(tile);         // not loaded: the first tile, or one named late
         // ---- (a) change masks ----
         const uint32_t k_wave = cur.k_tile + (uint32_t)wave * kWaveSpan;
-        uint4 nv[kIters];
+        uint4 nv[kIters];                              // the new patterns
+        uint4 pv[ARITH ? kIters : 1];                  // arithmetic payloads (difference, or new where it escapes)
+        uint32_t esc_all = 0;                          // bit 8 j + e: element e of vector j escapes
         uint32_t mask[kIters];
         // Always taken from the load registers, also for a tile that has no 128-bit loads (its
         // result is replaced below): this way every path consumes what was loaded, and the
@@ -852,12 +917,22 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         for (int j = 0; j < kIters; ++j) {
             nv[j] = raw_to_bf16(raw_new, j);
             mask[j] = nz16_mask(xor4(raw_old.v[j], nv[j]));
+            if constexpr (ARITH) {
+                uint32_t esc8;
+                pv[j] = arith_vec(raw_old.v[j], nv[j], &esc8);
+                esc_all |= esc8 << (8 * j);
+            }
         }
         // pin the above here: the load registers are dead from this point on, whatever the
         // scheduler would prefer
 #pragma unroll
         for (int j = 0; j < kIters; ++j)
             asm volatile("" : "+v"(mask[j]), "+v"(nv[j].x), "+v"(nv[j].y), "+v"(nv[j].z), "+v"(nv[j].w));
+        if constexpr (ARITH) {
+#pragma unroll
+            for (int j = 0; j < kIters; ++j) asm volatile("" : "+v"(pv[j].x), "+v"(pv[j].y), "+v"(pv[j].z), "+v"(pv[j].w));
+            asm volatile("" : "+v"(esc_all));
+        }
         if (cur.vec & 1u) {
             if (cur.limit != 0xFFFFFFFFu) {            // vectors past the end of the piece hold nothing
 #pragma unroll
@@ -873,11 +948,18 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                     uint4 o = load_vec_general<0>(c.old_base, c.pc, ks);
                     uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, ks);
                     uint32_t m = nz16_mask(xor4(o, n));
+                    uint32_t esc8 = 0;
+                    uint4 pay = n;
+                    if constexpr (ARITH) pay = arith_vec(o, n, &esc8);
 #pragma unroll
                     for (int jj = 0; jj < kIters; ++jj) {
                         if ((uint32_t)jj == js) {
                             nv[jj] = n;
                             mask[jj] = m;
+                            if constexpr (ARITH) {
+                                pv[jj] = pay;
+                                esc_all = (esc_all & ~(0xFFu << (8 * jj))) | (esc8 << (8 * jj));
+                            }
                         }
                     }
                 }
@@ -893,11 +975,18 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 uint4 o = load_vec_general<0>(c.old_base, c.pc, k);
                 uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, k);
                 uint32_t m = nz16_mask(xor4(o, n));
+                uint32_t esc8 = 0;
+                uint4 pay = n;
+                if constexpr (ARITH) pay = arith_vec(o, n, &esc8);
 #pragma unroll
                 for (int jj = 0; jj < kIters; ++jj) {
                     if (jj == j) {
                         nv[jj] = n;
                         mask[jj] = m;
+                        if constexpr (ARITH) {
+                            pv[jj] = pay;
+                            esc_all = (esc_all & ~(0xFFu << (8 * jj))) | (esc8 << (8 * jj));
+                        }
                     }
                 }
             }
@@ -906,7 +995,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         // ---- (b) poll answers and ticket of the previous iteration; copy out what was announced ----
         const bool accept_now = ticket_out;
         if (accept_now && threadIdx.x == 0) {
-            s_ticket[parity] = (int32_t)ticket_take<NEW_F32>();   // nothing else is in flight here
+            s_ticket[parity] = (int32_t)ticket_take<WIDE>();   // nothing else is in flight here
         }
         ticket_out = false;
         if (wave == 0 && lane < n_polled && !has_prefix(wq_w)) wq_w = polled;
@@ -929,7 +1018,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         n_polled = q_len;
         // ask for the next ticket as soon as the one fetched ahead has been taken into use
         if (!walk.have_next && !accept_now && !walk.exhausted && !walk.redo) {
-            if (threadIdx.x == 0) ticket_request<NEW_F32>(a.ticket);
+            if (threadIdx.x == 0) ticket_request<WIDE>(a.ticket);
             ticket_out = true;
         }
 
@@ -1006,7 +1095,11 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 while (m && !(ROSE_DIAG & 8)) {
                     const uint32_t e = __ffs(m) - 1;
                     m &= m - 1;
-                    s_ring[slot & (kRing - 1)] = ((in_tile0 + e) << 16) | (pick16(nv[j], e) & 0xFFFFu);
+                    if constexpr (ARITH)
+                        s_ring[slot & (kRing - 1)] = ((in_tile0 + e) << 16) | (pick16(pv[j], e) & 0xFFFFu) |
+                                                     ((esc_all >> (8 * j + e)) << 31);
+                    else
+                        s_ring[slot & (kRing - 1)] = ((in_tile0 + e) << 16) | (pick16(nv[j], e) & 0xFFFFu);
                     ++slot;
                 }
             }
@@ -1072,8 +1165,14 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                         const uint32_t e = __ffs(m) - 1;
                         m &= m - 1;
                         if (pos < (u64)b.capacity) {
-                            b.idx[pos] = (int32_t)(cur.piece >= 0 ? dst_index(big_pc, local0 + e, false) : local0 + e);
-                            b.val[pos] = (uint16_t)pick16(nv[j], e);
+                            uint32_t local = cur.piece >= 0 ? dst_index(big_pc, local0 + e, false) : local0 + e;
+                            if constexpr (ARITH) {
+                                local |= (esc_all >> (8 * j + e)) << 31;
+                                b.val[pos] = (uint16_t)pick16(pv[j], e);
+                            } else {
+                                b.val[pos] = (uint16_t)pick16(nv[j], e);
+                            }
+                            b.idx[pos] = (int32_t)local;
                         }
                         ++pos;
                     }
@@ -1168,29 +1267,26 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 }
 
 // The instantiations get their own register budgets: 4 waves per SIMD (128 VGPRs) fit the bf16
-// kernel without spills, the fp32-master kernel holds twice the raw data and gets 3.  REFRESH = 1
-// also writes the new bf16 values over the old ones (rose_delta_encode_refresh).
-template <int NEW_F32, int REFRESH> __global__ void encode_kernel(EncodeArgs a);
-template <>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4), amdgpu_num_vgpr(kNumVgprBf16)))
-void encode_kernel<0, 0>(EncodeArgs a) {
-    encode_body<0, 0>(a);
-}
-template <>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4), amdgpu_num_vgpr(kNumVgprBf16)))
-void encode_kernel<0, 1>(EncodeArgs a) {
-    encode_body<0, 1>(a);
-}
-template <>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3), amdgpu_num_vgpr(kNumVgprF32)))
-void encode_kernel<1, 0>(EncodeArgs a) {
-    encode_body<1, 0>(a);
-}
-template <>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3), amdgpu_num_vgpr(kNumVgprF32)))
-void encode_kernel<1, 1>(EncodeArgs a) {
-    encode_body<1, 1>(a);
-}
+// kernels without spills; the fp32-master kernels hold twice the raw data, and the kernel that both
+// refreshes and forms arithmetic payloads keeps new values and payloads side by side: those get 3
+// (the one that does all three at once: 2).
+// REFRESH = 1 also writes the new bf16 values over the old ones; ARITH = 1 emits arithmetic payloads.
+template <int NEW_F32, int REFRESH, int ARITH> __global__ void encode_kernel(EncodeArgs a);
+#define ROSE_ENCODE_KERNEL(F32, REFRESH, ARITH, WAVES, VGPRS)                                                         \
+    template <>                                                                                                       \
+    __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES), amdgpu_num_vgpr(VGPRS))) \
+    void encode_kernel<F32, REFRESH, ARITH>(EncodeArgs a) {                                                           \
+        encode_body<F32, REFRESH, ARITH>(a);                                                                          \
+    }
+ROSE_ENCODE_KERNEL(0, 0, 0, 4, kNumVgpr0)
+ROSE_ENCODE_KERNEL(0, 1, 0, 4, kNumVgpr0)
+ROSE_ENCODE_KERNEL(0, 0, 1, 4, kNumVgpr0)
+ROSE_ENCODE_KERNEL(0, 1, 1, 3, kNumVgpr1)
+ROSE_ENCODE_KERNEL(1, 0, 0, 3, kNumVgpr1)
+ROSE_ENCODE_KERNEL(1, 1, 0, 3, kNumVgpr1)
+ROSE_ENCODE_KERNEL(1, 0, 1, 3, kNumVgpr1)
+ROSE_ENCODE_KERNEL(1, 1, 1, 2, kNumVgpr2)
+#undef ROSE_ENCODE_KERNEL
 
 // Replicated tensors after an encode with refresh: old <- bf16(new), whole tensors (they are small).
 __global__ __launch_bounds__(256) void refresh_replicated_kernel(const int32_t *list, const int64_t *numel, int32_t n,
@@ -1255,8 +1351,17 @@ __device__ __forceinline__ int32_t wave_find_segment(const int64_t *seg_off, int
     return lo;
 }
 
+// value an entry leaves at its element: the payload itself, or (arithmetic payload, no escape)
+// bf16(current + payload), see arith_pair
+__device__ __forceinline__ uint16_t apply_value(uint32_t cur, uint32_t val, bool add) {
+    if (!add) return (uint16_t)val;
+    return (uint16_t)pack_bf16_pair(__uint_as_float(cur << 16) + __uint_as_float(val << 16), 0.0f);
+}
+
+// arith != 0: the bucket holds arithmetic payloads (bit 31 of an index marks an entry that carries
+// the new pattern instead)
 __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel,
-                                           void *const *dst_ptrs) {
+                                           void *const *dst_ptrs, int arith) {
     __shared__ uint4 s_line[kApplyWaves][64][4];        // wave, line slot, 16-byte part
     __shared__ u64 s_addr[kApplyWaves][64];             // address of the line
     __shared__ int32_t s_parts[kApplyWaves][64];        // 16-byte parts of the line inside the tensor
@@ -1269,17 +1374,20 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
         const int64_t e = wbase + lane, e2 = e + 64;
         const bool valid = e < total;
         // everything that depends on the entry numbers alone is requested first
+        const int32_t idx_mask = arith ? 0x7FFFFFFF : -1;
 #if ROSE_APPLY_NT & 1
-        const int32_t idx = valid ? __builtin_nontemporal_load(b.idx + e) : 0;
+        const int32_t idx_raw = valid ? __builtin_nontemporal_load(b.idx + e) : 0;
         const uint32_t val = valid ? __builtin_nontemporal_load(b.val + e) : 0u;
 #else
-        const int32_t idx = valid ? b.idx[e] : 0;
+        const int32_t idx_raw = valid ? b.idx[e] : 0;
         const uint32_t val = valid ? b.val[e] : 0u;
 #endif
-        const int32_t idx_before = (lane == 0 && wbase > 0) ? b.idx[wbase - 1] : 0;
+        const int32_t idx_before = ((lane == 0 && wbase > 0) ? b.idx[wbase - 1] : 0) & idx_mask;
         const bool look = lane < kLineElems && e2 < total;
-        const int32_t idx2 = look ? b.idx[e2] : 0;
+        const int32_t idx2_raw = look ? b.idx[e2] : 0;
         const uint32_t val2 = look ? b.val[e2] : 0u;
+        const int32_t idx = idx_raw & idx_mask, idx2 = idx2_raw & idx_mask;
+        const bool add = arith && idx_raw >= 0, add2 = arith && idx2_raw >= 0;
 
         // tensor of the wave's first entry, then of each lane's entry
         int32_t t = wave_find_segment(b.seg_off, n_tensors, wbase, lane);
@@ -1292,7 +1400,7 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
         uint16_t *dst = valid ? static_cast<uint16_t *>(dst_ptrs[t]) : nullptr;
         const int32_t numel = valid ? local_numel[t] : 0;
         // may this entry go through the line path?  (depends on the entry alone)
-        const bool ok = valid && (((uintptr_t)dst) & 15u) == 0 && (idx | 7) < numel;
+        const bool ok = valid && (((uintptr_t)dst) & 15u) == 0 && idx >= 0 && (idx | 7) < numel;
         const u64 key = valid ? (((u64)(uint32_t)t << 32) | (uint32_t)(idx >> kLineShift)) : ~0ull;
 
         // same line as the entry before?  lane 0 looks at the last entry of the previous chunk
@@ -1304,7 +1412,7 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
         const u64 not_same = __ballot(!same);
         const int first_own = not_same ? __ffsll((long long)not_same) - 1 : 64;
         const bool owned = ok && lane >= first_own;
-        const bool direct = valid && !ok;
+        const bool direct = valid && !ok && idx >= 0 && idx < numel;   // an index outside the tensor is dropped
 
         // entries of the next chunk that still lie in this chunk's last line
         const u64 key63 = __shfl(key, 63, 64);
@@ -1312,7 +1420,8 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
         const int64_t seg_end63 = __shfl(seg_end, 63, 64);
         const int32_t numel63 = __shfl(numel, 63, 64);
         const bool ext = own63 && look && e2 < seg_end63 &&
-                         ((key63 & ~0xffffffffull) | (uint32_t)(idx2 >> kLineShift)) == key63 && (idx2 | 7) < numel63;
+                         ((key63 & ~0xffffffffull) | (uint32_t)(idx2 >> kLineShift)) == key63 && idx2 >= 0 &&
+                         (idx2 | 7) < numel63;
 
         // distinct lines of the owned entries
         const bool prev_owned = __shfl_up((int)owned, 1, 64) != 0 && lane > 0;
@@ -1342,8 +1451,14 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
 
         // patch
         uint16_t *lines16 = reinterpret_cast<uint16_t *>(&s_line[wave][0][0]);
-        if (owned) lines16[slot * kLineElems + (idx & (kLineElems - 1))] = (uint16_t)val;
-        if (ext) lines16[(n_lines - 1) * kLineElems + (idx2 & (kLineElems - 1))] = (uint16_t)val2;
+        if (owned) {
+            uint16_t *q = lines16 + slot * kLineElems + (idx & (kLineElems - 1));
+            *q = apply_value(*q, val, add);
+        }
+        if (ext) {
+            uint16_t *q = lines16 + (n_lines - 1) * kLineElems + (idx2 & (kLineElems - 1));
+            *q = apply_value(*q, val2, add2);
+        }
         lds_wave_fence();
 
         // store the lines back whole
@@ -1360,18 +1475,21 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
                 gstore16(reinterpret_cast<char *>((uintptr_t)s_addr[wave][sl]) + part * 16, s_line[wave][sl][part]);
 #endif
         }
+        if (direct) {
+            const uint16_t v = apply_value(add ? dst[idx] : 0u, val, add);
 #if ROSE_APPLY_NT & 8
-        if (direct) __builtin_nontemporal_store((uint16_t)val, dst + idx);
+            __builtin_nontemporal_store(v, dst + idx);
 #else
-        if (direct) dst[idx] = (uint16_t)val;
+            dst[idx] = v;
 #endif
+        }
         lds_wave_fence();                               // the LDS slots are reused by the next round
     }
 }
 
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors,
-                                                              const int32_t *local_numel, void *const *dst_ptrs) {
-    apply_body(b, n_tensors, local_numel, dst_ptrs);
+                                                              const int32_t *local_numel, void *const *dst_ptrs, int arith) {
+    apply_body(b, n_tensors, local_numel, dst_ptrs, arith);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1387,7 +1505,7 @@ __host__ __device__ inline size_t object_size(int32_t n_tensors, int64_t n) {
 }
 
 __global__ __launch_bounds__(256) void pack_kernel(BucketDev b, int32_t shard, int32_t n_tensors, int64_t first,
-                                                   int64_t n, char *obj) {
+                                                   int64_t n, int32_t payload, char *obj) {
     int64_t total = b.seg_off[n_tensors];
     if (total > b.capacity) total = b.capacity;
     const bool ok = total >= 0 && first + n <= total;          // else: an object nobody will apply
@@ -1403,6 +1521,7 @@ __global__ __launch_bounds__(256) void pack_kernel(BucketDev b, int32_t shard, i
             if (threadIdx.x == 5) w = (uint32_t)((u64)first >> 32);
             if (threadIdx.x == 6) w = (uint32_t)(u64)n;
             if (threadIdx.x == 7) w = (uint32_t)((u64)n >> 32);
+            if (threadIdx.x == 8) w = (uint32_t)payload;
             reinterpret_cast<uint32_t *>(obj)[threadIdx.x] = w;
         }
         int64_t *seg = reinterpret_cast<int64_t *>(obj + 64);
@@ -1431,14 +1550,15 @@ __host__ __device__ inline bool object_header_ok(const uint32_t *h, int32_t n_te
     const int64_t n = (int64_t)((u64)h[6] | ((u64)h[7] << 32));
     *n_out = n;
     if (h[0] != ROSE_OBJECT_MAGIC || h[1] != 1u || (int32_t)h[3] != n_tensors || first < 0 || n < 0) return false;
+    if (h[8] > 1u) return false;                                        // payload kind: 0 new pattern, 1 arithmetic
     if (n > (int64_t)(object_bytes / 6)) return false;
     return object_size(n_tensors, n) <= object_bytes;
 }
 
 __global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char *obj, size_t object_bytes, int32_t n_tensors,
                                                                      const int32_t *local_numel, void *const *dst_ptrs) {
-    uint32_t h[8];
-    for (int i = 0; i < 8; ++i) h[i] = reinterpret_cast<const uint32_t *>(obj)[i];
+    uint32_t h[9];
+    for (int i = 0; i < 9; ++i) h[i] = reinterpret_cast<const uint32_t *>(obj)[i];
     int64_t n;
     if (!object_header_ok(h, n_tensors, object_bytes, &n)) return;     // uniform: every thread leaves
     const size_t a_off = object_idx_off(n_tensors), b_off = a_off + up16(4 * (size_t)n);
@@ -1448,7 +1568,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char 
     b.capacity = n;
     b.seg_off = reinterpret_cast<int64_t *>(const_cast<char *>(obj + 64));
     if (b.seg_off[0] != 0 || b.seg_off[n_tensors] != n) return;
-    apply_body(b, n_tensors, local_numel, dst_ptrs);
+    apply_body(b, n_tensors, local_numel, dst_ptrs, (int)h[8]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1556,25 +1676,31 @@ __global__ __launch_bounds__(256) void bw_mix_kernel(const uint4 *a, const uint4
 #define ROSE_WGS_PER_CU 8
 #endif
 
+// the encode kernel variant for (fp32 master input, sender refresh, arithmetic payload)
+typedef void (*EncodeKernel)(EncodeArgs);
+static EncodeKernel encode_variant(int new_is_f32, int refresh, int arith) {
+    static const EncodeKernel table[8] = {encode_kernel<0, 0, 0>, encode_kernel<1, 0, 0>, encode_kernel<0, 1, 0>,
+                                          encode_kernel<1, 1, 0>, encode_kernel<0, 0, 1>, encode_kernel<1, 0, 1>,
+                                          encode_kernel<0, 1, 1>, encode_kernel<1, 1, 1>};
+    return table[(new_is_f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0)];
+}
+
 // Number of workgroups that fit on the device at once for the encode kernel.
-static int encode_resident(int new_is_f32, int refresh, int *resident) {
-    static int cached_all[4] = {0, 0, 0, 0};      // per kernel variant; the device set is homogeneous
-    int *cached = cached_all + 2 * refresh;
-    if (!cached[new_is_f32]) {
+static int encode_resident(int new_is_f32, int refresh, int arith, int *resident) {
+    static int cached[8] = {0, 0, 0, 0, 0, 0, 0, 0};      // per kernel variant; the device set is homogeneous
+    const int v = (new_is_f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0);
+    if (!cached[v]) {
         int dev = 0, cus = 0, per_cu = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = refresh ? (new_is_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<1, 1>, kThreads, 0)
-                                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<0, 1>, kThreads, 0))
-                        : (new_is_f32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<1, 0>, kThreads, 0)
-                                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_kernel<0, 0>, kThreads, 0));
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_variant(new_is_f32, refresh, arith), kThreads, 0);
         if (e != hipSuccess) return (int)e;
         if (per_cu < 1 || cus < 1) return (int)hipErrorInvalidValue;
         if (per_cu > ROSE_WGS_PER_CU) per_cu = ROSE_WGS_PER_CU;
-        cached[new_is_f32] = cus * per_cu;
+        cached[v] = cus * per_cu;
     }
-    *resident = cached[new_is_f32];
+    *resident = cached[v];
     return 0;
 }
 
@@ -1582,11 +1708,11 @@ static int encode_resident(int new_is_f32, int refresh, int *resident) {
 #define ROSE_SERVER_WGS 16          // workgroups of the grid that serve prefixes (kWaves servers each)
 #endif
 
-int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, void *stream) {
+int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, int arith, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     EncodeArgs a = args;
     int resident = 0;
-    int rc = encode_resident(new_is_f32, refresh ? 1 : 0, &resident);
+    int rc = encode_resident(new_is_f32, refresh ? 1 : 0, arith, &resident);
     if (rc) return rc;
     // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
     // a quarter of what is resident.  They are the first workgroups of the grid, so they are
@@ -1618,35 +1744,32 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *ref
     if (reset_blocks > 2048) reset_blocks = 2048;
     hipLaunchKernelGGL(reset_kernel, dim3(reset_blocks), dim3(256), 0, st, reinterpret_cast<u64 *>(a.abort_flag), n_words);
     const dim3 grid(workers + server_wgs), block(kThreads);
+    hipLaunchKernelGGL(encode_variant(new_is_f32, refresh ? 1 : 0, arith), grid, block, 0, st, a);
     if (refresh) {
-        if (new_is_f32) hipLaunchKernelGGL((encode_kernel<1, 1>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((encode_kernel<0, 1>), grid, block, 0, st, a);
         if (refresh->n > 0)
             hipLaunchKernelGGL(refresh_replicated_kernel, dim3(8, refresh->n > 1024 ? 1024 : refresh->n), dim3(256), 0, st,
                                refresh->list, refresh->numel, refresh->n, const_cast<void *const *>(a.old_ptrs),
                                a.new_ptrs, new_is_f32);
-    } else {
-        if (new_is_f32) hipLaunchKernelGGL((encode_kernel<1, 0>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((encode_kernel<0, 0>), grid, block, 0, st, a);
     }
     hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, st, a);
     return (int)hipGetLastError();
 }
 
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
-                 void *stream) {
+                 int arith, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = (b.capacity + kApplyThreads - 1) / kApplyThreads;
     int blocks = chunks < 1 ? 1 : (chunks > 256 * 32 ? 256 * 32 : (int)chunks);
-    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs);
+    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs, arith);
     return (int)hipGetLastError();
 }
 
-int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, void *object, void *stream) {
+int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, int32_t payload,
+                void *object, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t want = (n + 1023) / 1024;
     int blocks = want < 1 ? 1 : (want > 256 * 16 ? 256 * 16 : (int)want);
-    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, b, shard, n_tensors, first, n, static_cast<char *>(object));
+    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, b, shard, n_tensors, first, n, payload, static_cast<char *>(object));
     return (int)hipGetLastError();
 }
 

@@ -124,11 +124,12 @@ struct RefreshArgs {
     const int64_t *numel;
     int32_t n;
 };
-int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, void *stream);
+int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, int arith, void *stream);
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
-                 void *stream);
+                 int arith, void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
-int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, void *object, void *stream);
+int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, int32_t payload,
+                void *object, void *stream);
 int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, const int32_t *local_numel,
                         void *const *dst_ptrs, void *stream);
 size_t object_bytes_for(int32_t n_tensors, int64_t n);

@@ -46,7 +46,7 @@ def new_as_bf16(n):
     return n.to(torch.bfloat16) if n.dtype == torch.float32 else n
 
 
-def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None, **kw):
+def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None, arith=False, **kw):
     dev = "cuda"
     olds, news = [], []
     for _, _, o, n in synth.model_pairs(tensors, recipe, seed, dev, **kw):
@@ -60,7 +60,10 @@ def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None
         cap_frac = min(1.0, 1.3 * density + 0.002)
     buckets = [R.Bucket(int(plan.bucket_capacity(d) * cap_frac) + 4096, len(tensors)) for d in range(tp)]
     print("  encode", flush=True)
-    R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
+    if arith:
+        R.delta_encode_ex(plan, old_tab, new_tab, new_dtype, R.ENCODE_ARITH, buckets, ws)
+    else:
+        R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
     torch.cuda.synchronize()
     totals = [R.bucket_check(plan, b) for b in buckets]
     seg = [b.seg_off.cpu().numpy() for b in buckets]
@@ -82,6 +85,8 @@ def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None
     print("  order", flush=True)
     for d in range(tp):
         idx = buckets[d].idx[:totals[d]]
+        if arith:
+            idx = idx & 0x7FFFFFFF                      # bit 31 marks an escaped entry
         if totals[d] > 1:
             drops = torch.nonzero(idx[1:] <= idx[:-1]).flatten() + 1
             starts = set(int(x) for x in seg[d])
@@ -95,6 +100,11 @@ def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None
                                     t["sections"], tp)
         for d in range(tp):
             a, b = int(seg[d][i]), int(seg[d][i + 1])
+            if arith:
+                old_local = oracle.dense_shard(host_bits(olds[i]), t["rows"], t["cols"], t["rule"], t["sections"], tp, d)
+                ab = oracle.arith_bucket({"idx": want[d][0], "val": want[d][1],
+                                          "seg_off": np.array([0, want[d][0].size], dtype=np.int64)}, [old_local])
+                want[d] = (ab["idx"], ab["val"])
             assert b - a == want[d][0].size, (i, d)
             assert np.array_equal(buckets[d].idx[a:b].cpu().numpy(), want[d][0]), (i, d)
             assert np.array_equal(buckets[d].val[a:b].cpu().numpy().view(np.uint16), want[d][1]), (i, d)
@@ -103,7 +113,10 @@ def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None
     print("  apply + round trip", flush=True)
     for d in range(tp):
         dst = [torch_shard(o, t, tp, d).clone() for t, o in zip(tensors, olds)]
-        R.delta_apply(plan, d, buckets[d], R.ptr_table(dst))
+        if arith:
+            R.delta_apply_ex(plan, d, buckets[d], R.PAYLOAD_ARITH, R.ptr_table(dst))
+        else:
+            R.delta_apply(plan, d, buckets[d], R.ptr_table(dst))
         torch.cuda.synchronize()
         for i, (t, n) in enumerate(zip(tensors, news)):
             want = torch_shard(new_as_bf16(n), t, tp, d)
@@ -129,6 +142,15 @@ def test_decoder7b_tp4_p05():
     totals = run_and_check(ts, 4, "bernoulli", 0, sample, density=0.05, p=0.05)
     n = models.numel(ts)
     assert abs(sum(totals) - 0.05 * n) < 6 * (n * 0.05 * 0.95) ** 0.5 + 0.05 * 4 * 65 * 4096
+
+
+def test_decoder7b_tp4_p05_arithmetic_payload():
+    """The same workload with arithmetic payloads (rounded differences, escapes where adding back
+    would not be exact): sampled tensors against the oracle, round trip on everything."""
+    print("case: decoder7b tp=4 p=0.05 seed=0 arith", flush=True)
+    ts = models.decoder_7b()
+    sample = [0, 1, 2, 3, 5, 6, len(ts) - 1]
+    run_and_check(ts, 4, "bernoulli", 0, sample, density=0.05, arith=True, p=0.05)
 
 
 @pytest.mark.parametrize("p", [0.001, 0.01, 0.1, 0.5])

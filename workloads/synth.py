@@ -59,6 +59,34 @@ def pair_bernoulli(numel, p, seed, device="cpu", chunk=1 << 28):
     return old, new
 
 
+def pair_any_patterns(numel, p, seed, device="cpu"):
+    """Value stress for the arithmetic payload: old = N(0, 0.02) bf16 with one element in eight
+    replaced by an arbitrary 16-bit pattern (infinities, NaNs, subnormals, both zeros) and one in
+    eight by a tiny value (exponent field 0..3); a Bernoulli(p) set of elements changes, a third of
+    them by +-1..3 ulp, a third to an arbitrary pattern, a third to a tiny value of either sign.
+    Returns flat (old, new) bf16 tensors."""
+    g = _gen(device, seed)
+    o = gen_old(numel, g, device).view(torch.int16).to(torch.int32) & 0xFFFF
+    anyp = torch.randint(0, 1 << 16, (numel,), generator=g, device=device, dtype=torch.int32)
+    tiny = torch.randint(0, 0x0200, (numel,), generator=g, device=device, dtype=torch.int32) | \
+        (torch.randint(0, 2, (numel,), generator=g, device=device, dtype=torch.int32) << 15)
+    kind_o = torch.randint(0, 8, (numel,), generator=g, device=device)
+    o = torch.where(kind_o == 0, anyp, torch.where(kind_o == 1, tiny, o))
+    old = (((o + 0x8000) & 0xFFFF) - 0x8000).to(torch.int16).view(torch.bfloat16)
+    mask = torch.rand(numel, generator=g, device=device) < p
+    kind_n = torch.randint(0, 3, (numel,), generator=g, device=device)
+    k = torch.randint(1, 4, (numel,), generator=g, device=device, dtype=torch.int32)
+    sgn = torch.randint(0, 2, (numel,), generator=g, device=device, dtype=torch.int32) * 2 - 1
+    near = ulp_shift(old, mask, k * sgn).view(torch.int16).to(torch.int32) & 0xFFFF
+    anyn = torch.randint(0, 1 << 16, (numel,), generator=g, device=device, dtype=torch.int32)
+    tinyn = torch.randint(0, 0x0200, (numel,), generator=g, device=device, dtype=torch.int32) | \
+        (torch.randint(0, 2, (numel,), generator=g, device=device, dtype=torch.int32) << 15)
+    n = torch.where(kind_n == 0, near, torch.where(kind_n == 1, anyn, tinyn))
+    n = torch.where(mask, n, o)
+    new = (((n + 0x8000) & 0xFFFF) - 0x8000).to(torch.int16).view(torch.bfloat16)
+    return old, new
+
+
 def pair_clustered_f32(rows, cols, seed, device="cpu", active_rows=None, sigma=1e-4):
     """fp32-master variant: new32 = float(old_bf16) + N(0, sigma^2) on selected elements,
     exact upcast elsewhere.  Row r gets its own change rate q_r ~ Beta(0.5, 20); with
@@ -98,6 +126,8 @@ def model_pairs(tensors, recipe, seed, device="cpu", **kw):
         s = tensor_seed(seed, i)
         if recipe == "bernoulli":
             old, new = pair_bernoulli(t["rows"] * t["cols"], kw["p"], s, device)
+        elif recipe == "any_patterns":
+            old, new = pair_any_patterns(t["rows"] * t["cols"], kw["p"], s, device)
         elif recipe == "clustered_f32":
             act = kw.get("vocab_active") if t["name"] in ("embed", "lm_head") else None
             old, new = pair_clustered_f32(t["rows"], t["cols"], s, device, active_rows=act)
