@@ -184,9 +184,14 @@ def test_decoder8b_shapes(tp):
 
 
 def test_decoder32b_tp8_fp32_master_clustered():
-    """fp32-master input with per-row Beta(0.5, 20) change rates, 32B shapes at 8 of 64 layers (the
-    full set with an fp32 copy does not leave room for the receiver's shards on one GPU)."""
-    print("case: decoder32b(8 layers) tp=8 clustered fp32 seed=0", flush=True)
-    ts = models.decoder_32b(layers=8)
+    """fp32-master input with per-row Beta(0.5, 20) change rates on the whole 32B-style set: old
+    (65.5 GB) and the fp32 new weights (131 GB) are resident, the receiver's shards are built and
+    checked one shard at a time."""
+    print("case: decoder32b tp=8 clustered fp32 seed=0", flush=True)
+    free, _ = torch.cuda.mem_get_info()
+    layers = 64 if free > 245e9 else 8
+    if layers != 64:
+        print("  only %.0f GB free: 8 of 64 layers" % (free / 1e9), flush=True)
+    ts = models.decoder_32b(layers=layers)
     sample = [0, 2, 3, 6, len(ts) - 1]
-    run_and_check(ts, 8, "clustered_f32", 0, sample, cap_frac=0.08, vocab_active=20000)
+    run_and_check(ts, 8, "clustered_f32", 0, sample, cap_frac=0.03, vocab_active=20000)
