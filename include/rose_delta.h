@@ -44,7 +44,7 @@ typedef enum {
     ROSE_ERR_CAPACITY = 3,    /* a bucket was too small (see rose_bucket_check) */
     ROSE_ERR_ALIGN = 4,       /* a bucket or workspace pointer is not aligned as required */
     ROSE_ERR_HIP = 5,         /* a HIP runtime call failed (no GPU, launch failure), or an encode launch gave up */
-    ROSE_ERR_UNSUPPORTED = 6  /* a shard-local tensor has 2^31 or more elements, tp > ROSE_MAX_TP */
+    ROSE_ERR_UNSUPPORTED = 6  /* a destination shard's local tensor has 2^31 or more elements, tp > ROSE_MAX_TP */
 } rose_status;
 
 /* How the receiver's layout cuts a row-major (rows, cols) tensor into tp shards. */

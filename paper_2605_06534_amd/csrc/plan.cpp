@@ -40,7 +40,9 @@ static bool magic_ok(uint32_t divisor, uint32_t magic, uint32_t shift, uint32_t 
 
 using rose::Piece;
 
-static rose_status check_desc(const rose_tensor_desc &t, int32_t tp) {
+// bound_local: also require the shard-local size to fit an int32 index (the destination side; a
+// sender's slice is addressed with 64-bit offsets and may be larger)
+static rose_status check_desc(const rose_tensor_desc &t, int32_t tp, bool bound_local) {
     if (t.rows < 0 || t.cols < 0) return ROSE_ERR_ARG;
     switch (t.rule) {
     case ROSE_REPLICATED: break;
@@ -67,7 +69,7 @@ static rose_status check_desc(const rose_tensor_desc &t, int32_t tp) {
     // guard rows * cols against int64 overflow, then bound the shard-local size
     if (t.cols != 0 && t.rows > (int64_t)(INT64_MAX / 4) / t.cols) return ROSE_ERR_UNSUPPORTED;
     int64_t local = t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : tp);
-    if (local >= (int64_t)1 << 31) return ROSE_ERR_UNSUPPORTED;
+    if (bound_local && local >= (int64_t)1 << 31) return ROSE_ERR_UNSUPPORTED;
     return ROSE_OK;
 }
 
@@ -189,8 +191,8 @@ extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensor
     if (!tensors || n_tensors < 1 || tp < 1 || tp_src < 1 || src_rank < 0 || src_rank >= tp_src) return ROSE_ERR_ARG;
     if (tp > ROSE_MAX_TP || tp_src > ROSE_MAX_TP) return ROSE_ERR_UNSUPPORTED;
     for (int32_t i = 0; i < n_tensors; ++i) {
-        rose_status s = check_desc(tensors[i], tp);
-        if (s == ROSE_OK) s = check_desc(tensors[i], tp_src);
+        rose_status s = check_desc(tensors[i], tp, true);
+        if (s == ROSE_OK) s = check_desc(tensors[i], tp_src, false);
         if (s == ROSE_OK && tensors[i].src_groups > 0 && tensors[i].src_groups % tp_src) s = ROSE_ERR_SHAPE;
         if (s != ROSE_OK) return s;
     }

@@ -195,3 +195,37 @@ def test_decoder32b_tp8_fp32_master_clustered():
     ts = models.decoder_32b(layers=layers)
     sample = [0, 2, 3, 6, len(ts) - 1]
     run_and_check(ts, 8, "clustered_f32", 0, sample, cap_frac=0.03, vocab_active=20000)
+
+
+def test_largest_local_tensor_two_shards():
+    """The largest local tensor the int32 index admits (2^31 - 8 elements per shard), two shards, so
+    that global element numbers pass 2^32: every entry against torch.nonzero on the shard's slice,
+    with changes planted at the first and last element of each shard."""
+    n = (1 << 31) - 8
+    print("case: 2 x (2^31 - 8) split rows tp=2 p=0.001 seed=5", flush=True)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40e9:
+        pytest.skip("needs about 35 GB of free device memory")
+    ts = [dict(name="big", rows=2, cols=n, rule=R.SPLIT_ROWS, sections=None)]
+    old, new = synth.pair_bernoulli(2 * n, 0.001, 5, "cuda")
+    ob, nb = old.view(torch.int16), new.view(torch.int16)
+    for g in (0, n - 1, n, 2 * n - 1):
+        nb[g] = ob[g] ^ 0x0101
+    plan = R.shard_plan(ts, 2)
+    ws = R.workspace(plan)
+    buckets = [R.Bucket(int(n * 0.0015), 1) for _ in range(2)]
+    R.delta_encode(plan, R.ptr_table([old]), R.ptr_table([new]), R.BF16, buckets, ws)
+    torch.cuda.synchronize()
+    for d in range(2):
+        o, w = ob[d * n:(d + 1) * n], nb[d * n:(d + 1) * n]
+        want = torch.nonzero(o != w).ravel()
+        total = R.bucket_check(plan, buckets[d])
+        assert total == want.numel()
+        assert int(want[0]) == 0 and int(want[-1]) == n - 1
+        assert torch.equal(buckets[d].idx[:total].long(), want)
+        assert torch.equal(buckets[d].val[:total].view(torch.int16), w[want])
+        dst = o.clone()
+        R.delta_apply(plan, d, buckets[d], R.ptr_table([dst]))
+        torch.cuda.synchronize()
+        assert torch.equal(dst, w)
+        del dst, want

@@ -170,6 +170,13 @@ def test_argument_errors():
             bad()
     # a 2^31 - 8 element flat tensor at TP = 1 is the largest accepted local size class
     assert plan(1, (1 << 31) - 8, R.REPLICATED, 1).local_numel(0, 0) == (1 << 31) - 8
+    # the bound is on the destination's local size: the sender's slice (here the whole tensor, past
+    # 2^32 elements) is addressed with 64-bit offsets
+    n = (1 << 31) - 8
+    big = plan(2, n, R.SPLIT_ROWS, 2)
+    assert big.local_numel(0, 1) == n and big.src_numel(0) == 2 * n
+    assert big.map_index(0, 2 * n - 1) == (1, 1, n - 1) and big.map_index(0, n) == (1, 1, 0)
+    assert big.map_index(0, n - 1) == (0, 1, n - 1)
 
 
 def test_empty_tensor_gets_a_tile():
