@@ -261,6 +261,14 @@ def main():
     dens = nnz_total / local_elems
     app_line_bytes = 6 * nnz_total + 2 * (1 - (1 - dens) ** 32) * 2 * local_elems
 
+    # HBM bytes per encode launch as counted by rocprofv3 (FETCH_SIZE x 2.0 + WRITE_SIZE KiB, two --pmc runs,
+    # scale factors from the copy probe): cannot be collected from inside this process, so the figure
+    # recorded in profiles/encode_apply_decoder7b_tp4_hbm_traffic.txt is reported for the workload it was
+    # taken on, and null for any other unless --traffic-bytes passes one in.
+    traffic = args.traffic_bytes
+    if (traffic is None and args.workload == "decoder7b_tp4" and args.density is None and args.layers is None
+            and args.tp_src == 1 and args.payload == "new" and args.seed == 0):
+        traffic = 29.70e9
     out = {
         "metric": "weight-delta encode+apply GB/s (bf16 scanned)",
         "value": round(value, 2),
@@ -276,7 +284,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "encode_kernel",
                      "achieved": round(enc_bytes / 1e9 / (t_enc / 1e3), 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(enc_bytes / 1e9 / (t_enc / 1e3) / HBM_PEAK_GBS, 4),
-                     "traffic": args.traffic_bytes,
+                     "traffic": traffic,
                      "algorithmic_bytes": enc_bytes, "launch_ms": round(t_enc, 4)},
         "detail": {"t_encode_ms": round(t_enc, 4), "t_apply_ms": round(t_app, 4),
                    "encode_scanned_GBs": round(scanned / 1e9 / (t_enc / 1e3), 1),
