@@ -1327,8 +1327,17 @@ __global__ __launch_bounds__(256) void refresh_replicated_kernel(const int32_t *
 #endif
 constexpr int kApplyThreads = 256;
 constexpr int kApplyWaves = kApplyThreads / 64;
-constexpr int kLineElems = 32;                  // 64-byte line of 16-bit elements
-constexpr int kLineShift = 5;
+#ifndef ROSE_APPLY_LINE
+#define ROSE_APPLY_LINE 64                      // bytes moved around an entry: 64 or 32 (32 halves the bytes at low
+                                                // density and is slower all the same: 7B workload 3.61 instead of
+                                                // 2.43 ms at 1 %, 7.91 instead of 5.20 ms at 5 %: the memory moves
+                                                // 64-byte units)
+#endif
+constexpr int kLineElems = ROSE_APPLY_LINE / 2; // line of 16-bit elements
+constexpr int kLineShift = ROSE_APPLY_LINE == 64 ? 5 : 4;
+constexpr int kLineParts = kLineElems / 8;      // 16-byte parts of a line
+constexpr int kLinesPerRound = 64 / kLineParts; // lines a wave moves with one load per lane
+static_assert(ROSE_APPLY_LINE == 64 || ROSE_APPLY_LINE == 32, "line size");
 
 __device__ __forceinline__ void lds_wave_fence() {
     // LDS operations of one wave are carried out in order; this keeps the compiler from moving
@@ -1362,7 +1371,7 @@ __device__ __forceinline__ uint16_t apply_value(uint32_t cur, uint32_t val, bool
 // the new pattern instead)
 __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel,
                                            void *const *dst_ptrs, int arith) {
-    __shared__ uint4 s_line[kApplyWaves][64][4];        // wave, line slot, 16-byte part
+    __shared__ uint4 s_line[kApplyWaves][64][kLineParts];   // wave, line slot, 16-byte part
     __shared__ u64 s_addr[kApplyWaves][64];             // address of the line
     __shared__ int32_t s_parts[kApplyWaves][64];        // 16-byte parts of the line inside the tensor
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1433,13 +1442,13 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
             const int32_t line_first = (idx >> kLineShift) << kLineShift;
             s_addr[wave][slot] = (u64)(uintptr_t)(dst + line_first);
             int32_t parts = (numel - line_first) >> 3;
-            s_parts[wave][slot] = parts > 4 ? 4 : parts;
+            s_parts[wave][slot] = parts > kLineParts ? kLineParts : parts;
         }
         lds_wave_fence();
 
-        // load the lines: four lanes per line, sixteen lines per round
-        for (int r = 0; r * 16 < n_lines; ++r) {
-            const int sl = r * 16 + (lane >> 2), part = lane & 3;
+        // load the lines: kLineParts lanes per line, kLinesPerRound lines per round
+        for (int r = 0; r * kLinesPerRound < n_lines; ++r) {
+            const int sl = r * kLinesPerRound + lane / kLineParts, part = lane % kLineParts;
             if (sl < n_lines && part < s_parts[wave][sl])
 #if ROSE_APPLY_NT & 2
                 s_line[wave][sl][part] = gload16_stream(reinterpret_cast<const char *>((uintptr_t)s_addr[wave][sl]) + part * 16);
@@ -1462,8 +1471,8 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
         lds_wave_fence();
 
         // store the lines back whole
-        for (int r = 0; r * 16 < n_lines; ++r) {
-            const int sl = r * 16 + (lane >> 2), part = lane & 3;
+        for (int r = 0; r * kLinesPerRound < n_lines; ++r) {
+            const int sl = r * kLinesPerRound + lane / kLineParts, part = lane % kLineParts;
             if (sl < n_lines && part < s_parts[wave][sl])
 #if ROSE_APPLY_NT & 4
                 {
