@@ -221,3 +221,83 @@ def test_arith_every_pattern_pair():
         torch.cuda.synchronize()
         assert torch.equal(dst.view(torch.int16), new.view(torch.int16)), "apply, block %04x" % o0
         del old, dst, pos, w_esc, w_val
+
+
+def test_arith_few_workers_dense_changes(monkeypatch):
+    """Arithmetic payloads through the regime where tiles are counted first and walked again (two
+    tickets of one group in a row) and where tiles are too dense to park, with and without refresh."""
+    ts = models.decoder(2, 1024, 16, 16, 64, 2816, 4096, fused=True)
+    pairs = 0
+    for workers, p, flags in [(66, 0.6, R.ENCODE_ARITH), (70, 0.9, R.ENCODE_ARITH | R.ENCODE_REFRESH),
+                              (97, 1.0, R.ENCODE_ARITH)]:
+        print("case: arith few workers=%d p=%g flags=%d" % (workers, p, flags), flush=True)
+        monkeypatch.setenv("ROSE_ENCODE_WORKERS", str(workers))
+        c = any_case(ts, 2, p, seed=workers)
+        check_arith(c, flags=flags)
+        pairs += int(c.ws.view(torch.int32)[2])
+    assert pairs > 0, "the pair handling never ran: the test does not reach what it is for"
+
+
+def test_arith_sender_side_sharding():
+    """A sender that holds its own slice only (degree 2, interleaved fused QKV) towards 4 destinations."""
+    print("case: arith sender-side sharding", flush=True)
+    ts = models.decoder(1, 256, 8, 4, 32, 704, 1024, fused=True)
+    for t in ts:
+        t["src_groups"] = 4 if t["name"].endswith("qkv") else 0
+    olds, news = [], []
+    for i, t, o, n in synth.model_pairs(ts, "any_patterns", 99, "cpu", p=0.1):
+        olds.append(o); news.append(n)
+    tp, tp_src = 4, 2
+    full_old, full_new = [bits(o) for o in olds], [bits(n) for n in news]
+    recs = [dict(t, old=o, new=n) for t, o, n in zip(ts, full_old, full_new)]
+    dst_old = [[oracle.dense_shard(r["old"], r["rows"], r["cols"], r["rule"], r["sections"], tp, d) for r in recs]
+               for d in range(tp)]
+    dst_new = [[oracle.dense_shard(r["new"], r["rows"], r["cols"], r["rule"], r["sections"], tp, d) for r in recs]
+               for d in range(tp)]
+    shards = [[torch.from_numpy(x.view(np.int16).copy()).cuda() for x in dst_old[d]] for d in range(tp)]
+    for s in range(tp_src):
+        plan = R.shard_plan(ts, tp, tp_src, s)
+        cut = R.shard_plan(ts, tp_src)                     # cuts the sender's slices with the library's dense path
+        so = [torch.empty(cut.local_numel(i, s), dtype=torch.bfloat16, device="cuda") for i in range(len(ts))]
+        sn = [torch.empty_like(x) for x in so]
+        # the sender's slices under its own (group-interleaved) layout come from the oracle
+        for i, r in enumerate(recs):
+            for src, dstt in ((r["old"], so[i]), (r["new"], sn[i])):
+                sl = oracle_src_slice(r, src, tp_src, s)
+                dstt.copy_(torch.from_numpy(sl.view(np.int16).copy()).view(torch.bfloat16))
+        buckets = [R.Bucket(plan.bucket_capacity(d), len(ts)) for d in range(tp)]
+        ws = R.workspace(plan)
+        R.delta_encode_ex(plan, R.ptr_table(so), R.ptr_table(sn), R.BF16, R.ENCODE_ARITH, buckets, ws)
+        torch.cuda.synchronize()
+        for d in range(tp):
+            per_t = [oracle.encode_tensor_src(bits(so[i]), bits(sn[i]), r["rows"], r["cols"], r["rule"], r["sections"],
+                                              tp, tp_src, s, sends_replicated=(i % tp_src == s),
+                                              src_groups=r.get("src_groups", 0))[d] for i, r in enumerate(recs)]
+            seg = np.zeros(len(ts) + 1, dtype=np.int64)
+            for i, (ix, _) in enumerate(per_t):
+                seg[i + 1] = seg[i] + ix.size
+            plain = {"idx": np.concatenate([x[0] for x in per_t]), "val": np.concatenate([x[1] for x in per_t]),
+                     "seg_off": seg}
+            want = oracle.arith_bucket(plain, dst_old[d])
+            n = R.bucket_check(plan, buckets[d])
+            got = {"idx": buckets[d].idx[:n].cpu().numpy(), "val": buckets[d].val[:n].cpu().numpy().view(np.uint16),
+                   "seg_off": buckets[d].seg_off.cpu().numpy()}
+            assert_buckets_equal(got, want, "sender %d shard %d" % (s, d))
+            R.delta_apply_ex(plan, d, buckets[d], R.PAYLOAD_ARITH, R.ptr_table(shards[d]))
+        torch.cuda.synchronize()
+    for d in range(tp):
+        for i in range(len(ts)):
+            assert np.array_equal(bits(shards[d][i]), dst_new[d][i]), (d, i)
+
+
+def oracle_src_slice(r, full_bits, tp_src, s):
+    """The sender's slice of a full tensor under the sender-side layout (numpy, test side): the plain
+    shard, or for a group-interleaved fused tensor an equal row block of the interleaved matrix."""
+    from test_oracle_src_sharding import interleave_by_groups
+    g = r.get("src_groups", 0)
+    x = full_bits.reshape(r["rows"], r["cols"])
+    if not g:
+        return np.ascontiguousarray(numpy_shard(x, r["rule"], r["sections"], tp_src, s)).ravel()
+    xi = interleave_by_groups(x, r["sections"], g)
+    per = r["rows"] // tp_src
+    return np.ascontiguousarray(xi[s * per:(s + 1) * per]).ravel()
