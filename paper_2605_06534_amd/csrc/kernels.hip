@@ -83,7 +83,7 @@ __device__ __forceinline__ uint32_t arith_pair(uint32_t o, uint32_t n, uint32_t 
     const float nl = __uint_as_float(n << 16), nh = __uint_as_float(n & 0xFFFF0000u);
     const uint32_t d = pack_bf16_pair(nl - ol, nh - oh);
     const uint32_t back = pack_bf16_pair(ol + __uint_as_float(d << 16), oh + __uint_as_float(d & 0xFFFF0000u));
-    // a half of `nan` is non-zero where d is a NaN: magnitude above the pattern of infinity
+    // a half of (mx ^ 0x7F80...) is non-zero where d is a NaN: magnitude above the pattern of infinity
     uint32_t mx;
     asm("v_pk_max_u16 %0, %1, %2" : "=v"(mx) : "v"(d & 0x7FFF7FFFu), "v"(0x7F807F80u));
     const uint32_t bad = (back ^ n) | (mx ^ 0x7F807F80u);
@@ -201,9 +201,10 @@ __device__ __forceinline__ uint32_t dst_index(const Piece &pc, uint32_t k, bool 
 // Tile loaders.  A lane's vector j holds the eight 16-bit patterns at piece-relative local indices
 // k .. k+7 with k = k_wave + (j * 64 + lane) * 8.
 //
-// Fast path: the whole tile lies inside the piece and every vector is 16-byte aligned, so all
-// loads are unconditional 128-bit loads issued back to back.  Loading (raw registers) is split
-// from conversion so that a tile's loads can be issued long before its data is needed.
+// load_raw / load_tile_fast (used by the dense copy): the whole tile lies inside the piece and
+// every vector is 16-byte aligned, so all loads are 128-bit loads issued back to back.  Loading
+// (raw registers) is split from conversion (fp32 -> bf16) so that a tile's loads can be issued long
+// before its data is needed; the encode kernel has its own loader for that (load_raw_pair).
 template <int SRC_F32> struct RawTile;
 template <> struct RawTile<0> { uint4 v[kIters]; };
 template <> struct RawTile<1> { uint4 lo[kIters], hi[kIters]; };
@@ -458,8 +459,8 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 }
 
 // ---------------------------------------------------------------------------------------------
-// encode: persistent workgroups.  Workgroups 0 .. n_workers-1 walk the tiles (worker w takes tiles
-// w, w + n_workers, ...), the remaining ones serve prefixes (above).
+// encode: persistent workgroups.  The first n_server_wgs workgroups serve prefixes (above), the
+// others are workers that walk the tiles their tickets name (see ticket_tile and struct Walk).
 //
 // Worker, per tile: (1) the tile's 128-bit loads were issued one tile earlier; XOR old and new
 // into an 8-bit change mask per vector, (2) copy out parked tiles whose prefixes have arrived,
@@ -545,8 +546,7 @@ __device__ __forceinline__ void raw_zero(int j, RawTile<0> &ro, RawTile<NEW_F32>
     if constexpr (NEW_F32) rn.lo[j] = rn.hi[j] = make_uint4(0, 0, 0, 0);
     else rn.v[j] = make_uint4(0, 0, 0, 0);
 }
-// one vector of the old and of the new tensor at element `off` from uniform bases (typed pointer
-// plus a 32-bit offset: the form that needs no 64-bit address arithmetic per lane)
+// one vector of the old and of the new tensor at element `off` from uniform bases
 template <int NEW_F32, typename OFF>
 __device__ __forceinline__ void load_raw_at(const uint16_t *o, const void *n, OFF off, int j, RawTile<0> &ro,
                                             RawTile<NEW_F32> &rn) {
