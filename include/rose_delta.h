@@ -277,7 +277,8 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
  *                     tensors; an object that fails the check changes nothing.  Same rule as
  *                     rose_delta_apply about concurrent writers of the destination.
  * rose_object_check   synchronises `stream`, reads the header back and returns ROSE_ERR_ARG for a
- *                     malformed object; shard / first_entry / n_entries (host, may be NULL).
+ *                     malformed object; shard / first_entry / n_entries / payload kind (host, each
+ *                     may be NULL).
  */
 #define ROSE_OBJECT_MAGIC 0x45534F52u
 rose_status rose_object_bytes(const rose_plan *plan, int64_t n_entries, size_t *bytes);
@@ -289,7 +290,7 @@ rose_status rose_bucket_pack_ex(const rose_plan *plan, int32_t d, const rose_buc
 rose_status rose_object_apply(const rose_plan *plan, const void *object, size_t object_bytes,
                               void *const *dst_ptrs, void *stream);
 rose_status rose_object_check(const rose_plan *plan, const void *object, size_t object_bytes, void *stream,
-                              int32_t *shard, int64_t *first_entry, int64_t *n_entries);
+                              int32_t *shard, int64_t *first_entry, int64_t *n_entries, int32_t *payload);
 
 /*
  * Bandwidth probe, for measuring what HBM delivers beside the kernels above: copies `bytes`

@@ -60,7 +60,7 @@ _SIGS = {
     "rose_bucket_pack": (_i32, [_vp, _i32, _P(CBucket), _i64, _i64, _vp, ctypes.c_size_t, _vp]),
     "rose_bucket_pack_ex": (_i32, [_vp, _i32, _P(CBucket), _i32, _i64, _i64, _vp, ctypes.c_size_t, _vp]),
     "rose_object_apply": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
-    "rose_object_check": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _P(_i32), _P(_i64), _P(_i64)]),
+    "rose_object_check": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _P(_i32), _P(_i64), _P(_i64), _P(_i32)]),
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
     "rose_bw_probe_mixed": (_i32, [_vp, _vp, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp]),
     "rose_status_str": (ctypes.c_char_p, [_i32]),
@@ -289,8 +289,10 @@ def object_apply(plan, obj, dst_tab, stream=None):
                                   _stream(stream)), "object_apply")
 
 
-def object_check(plan, obj, stream=None):
-    d, first, n = _i32(), _i64(), _i64()
+def object_check(plan, obj, stream=None, with_payload=False):
+    """-> (shard, first_entry, n_entries), with the payload kind appended if asked for."""
+    d, first, n, kind = _i32(), _i64(), _i64(), _i32()
     _check(_lib.rose_object_check(plan._h, obj.data_ptr(), obj.numel() * obj.element_size(), _stream(stream),
-                                  ctypes.byref(d), ctypes.byref(first), ctypes.byref(n)), "object_check")
-    return d.value, first.value, n.value
+                                  ctypes.byref(d), ctypes.byref(first), ctypes.byref(n), ctypes.byref(kind)),
+           "object_check")
+    return (d.value, first.value, n.value, kind.value) if with_payload else (d.value, first.value, n.value)

@@ -274,7 +274,8 @@ extern "C" rose_status rose_object_apply(const rose_plan *p, const void *object,
 }
 
 extern "C" rose_status rose_object_check(const rose_plan *p, const void *object, size_t object_bytes, void *stream,
-                                         int32_t *shard, int64_t *first_entry, int64_t *n_entries) {
+                                         int32_t *shard, int64_t *first_entry, int64_t *n_entries,
+                                         int32_t *payload) {
     if (!p || !object || object_bytes < 64) return ROSE_ERR_ARG;
     uint32_t h[16];
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -286,5 +287,6 @@ extern "C" rose_status rose_object_check(const rose_plan *p, const void *object,
     if (shard) *shard = (int32_t)h[2];
     if (first_entry) *first_entry = (int64_t)((uint64_t)h[4] | ((uint64_t)h[5] << 32));
     if (n_entries) *n_entries = n;
+    if (payload) *payload = (int32_t)h[8];
     return ROSE_OK;
 }

@@ -54,6 +54,7 @@ def check_arith(c, flags=R.ENCODE_ARITH, objects=False, min_escape=None):
             for a, b in zip(cuts[:-1], cuts[1:]):
                 obj = torch.empty(R.object_bytes(c.plan, b - a), dtype=torch.uint8, device="cuda")
                 R.bucket_pack_ex(c.plan, d, c.buckets[d], R.PAYLOAD_ARITH, a, b - a, obj)
+                assert R.object_check(c.plan, obj, with_payload=True) == (d, a, b - a, R.PAYLOAD_ARITH)
                 objs.append(obj)
             for obj in reversed(objs):                    # any order
                 R.object_apply(c.plan, obj, tab)

@@ -44,6 +44,7 @@ def test_objects_equal_oracle_and_apply_in_any_order(chunk):
             ref = oracle.pack_object(want[d], d, first, n)
             assert np.array_equal(objs[k].cpu().numpy(), ref), (d, k)
             assert R.object_check(c.plan, objs[k]) == (d, first, n)
+            assert R.object_check(c.plan, objs[k], with_payload=True)[3] == R.PAYLOAD_NEW
         old_bits = [r["old"] for r in recs]
         dst = c.shard_init(d, old_bits)
         tab = R.ptr_table(dst)
