@@ -164,6 +164,12 @@ rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
  * seg_off[n_tensors] of every bucket is set to -1, rose_bucket_check returns ROSE_ERR_HIP and
  * rose_delta_apply of such a bucket does nothing.
  *
+ * The grid is sized so that all of its workgroups fit on the device at once, and progress is
+ * argued for that case.  Kernels of other streams that hold compute units while the launch runs
+ * only delay it as long as they end; two encode launches running at the same time on one device
+ * (different streams, different workspaces) can starve each other until the bounded wait gives up:
+ * order encode launches of one device on one stream.
+ *
  * Environment: ROSE_ENCODE_WORKERS=<n> (read at every call) caps the number of workgroups that
  * walk tiles, e.g. to leave compute units to other kernels; values of 64 or less, or above what
  * the device holds, are ignored.  After a launch the 32-bit word 2 of the workspace holds a
