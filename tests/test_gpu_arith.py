@@ -49,7 +49,7 @@ def check_arith(c, flags=R.ENCODE_ARITH, objects=False, min_escape=None):
         tab = R.ptr_table(dst)
         if objects:
             total = int(want["seg_off"][-1])
-            cuts = sorted({0, total // 3, total // 3 + 1, (2 * total) // 3, total})
+            cuts = sorted({0, total // 3, min(total, total // 3 + 1), (2 * total) // 3, total})
             objs = []
             for a, b in zip(cuts[:-1], cuts[1:]):
                 obj = torch.empty(R.object_bytes(c.plan, b - a), dtype=torch.uint8, device="cuda")
