@@ -172,8 +172,10 @@ rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
  *
  * Environment: ROSE_ENCODE_WORKERS=<n> (read at every call) caps the number of workgroups that
  * walk tiles, e.g. to leave compute units to other kernels; values of 64 or less, or above what
- * the device holds, are ignored.  After a launch the 32-bit word 2 of the workspace holds a
- * diagnostic count (how often a workgroup received two tickets of one group of blocks in a row).
+ * the device holds, are ignored.  After a launch the 32-bit words 2 and 3 of the workspace hold
+ * diagnostic counts (how often a workgroup received two tickets of one group of blocks in a row;
+ * how often it counted a ticket's remaining tiles ahead of a wait, which happens where more than
+ * about a third of the elements change).
  */
 rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs,
                               const void *const *new_ptrs, int32_t new_dtype,

@@ -309,6 +309,9 @@ constexpr u64 kValueMask = (1ull << kStatusShift) - 1;
 #define ROSE_DIAG 0           // timing experiments only: 1 no waiting for prefixes, 2 no bucket writes,
                               // 4 no publishing, 8 no parking in LDS
 #endif
+#ifndef ROSE_COUNT_AHEAD
+#define ROSE_COUNT_AHEAD 1    // count the rest of a ticket's tiles before waiting for room (dense inputs)
+#endif
 #ifndef ROSE_SPIN_LIMIT
 #define ROSE_SPIN_LIMIT (1u << 22)   // failed polls after which a wave gives up and flags the launch
 #endif
@@ -605,6 +608,11 @@ __device__ __forceinline__ int32_t ticket_tile(const EncodeArgs &a, int32_t tick
 // accepted nothing waits until the counts of all tiles of both tickets are published by a
 // count-only pass; then those tiles are walked again ("redo", without publishing) in the normal
 // way.  While redoing, no further ticket is asked for.
+// The same machinery serves tiles so dense that the ring does not hold a ticket's worth of them: a
+// worker that would have to wait for room with fewer tiles parked than a ticket has, and with tiles
+// of the current ticket still uncounted, counts those first and walks the ticket again from the
+// current tile on.  (Waiting there is allowed by the rule above, but every later group of workers
+// would wait for those counts in turn, and the groups would run one after the other.)
 struct Walk {
     int32_t ticket, j;          // ticket in use (-1: none yet) and its batch slot
     int32_t next_ticket;        // ticket fetched ahead of time
@@ -836,12 +844,32 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     auto publish_count = [&](int32_t t) {
         const TileCtx c = tile_ctx(a, __builtin_amdgcn_readfirstlane(t));
         uint32_t cnt = 0;
+        if ((c.vec & 1u) && c.limit == 0xFFFFFFFFu) {
+            // a whole tile with 128-bit loads (cached: the tile is read again soon); kept rolled, one
+            // pair of vectors at a time, because the next tile's loads occupy the load registers
 #pragma unroll 1
-        for (int j = 0; j < kIters; ++j) {
-            const uint32_t k = c.k_tile + (uint32_t)wave * kWaveSpan + (uint32_t)(j * 64 + lane) * kVec;
-            const uint4 o = load_vec_general<0>(c.old_base, c.pc, k);
-            const uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, k);
-            cnt += __popc(nz16_mask(xor4(o, n)));
+            for (int j = 0; j < kIters; ++j) {
+                const uint32_t k = c.k_tile + (uint32_t)wave * kWaveSpan + (uint32_t)(j * 64 + lane) * kVec;
+                const int64_t e = src_index(c.pc, k, true);
+                const uint4 o = gload16(c.old_base + e);
+                uint4 n;
+                if constexpr (NEW_F32) {
+                    const uint32_t *p32 = static_cast<const uint32_t *>(c.new_base) + e;
+                    const uint4 lo = gload16(p32), hi = gload16(p32 + 4);
+                    n = make_uint4(pack_rne(lo.x, lo.y), pack_rne(lo.z, lo.w), pack_rne(hi.x, hi.y), pack_rne(hi.z, hi.w));
+                } else {
+                    n = gload16(static_cast<const uint16_t *>(c.new_base) + e);
+                }
+                cnt += __popc(nz16_mask(xor4(o, n)));
+            }
+        } else {
+#pragma unroll 1
+            for (int j = 0; j < kIters; ++j) {
+                const uint32_t k = c.k_tile + (uint32_t)wave * kWaveSpan + (uint32_t)(j * 64 + lane) * kVec;
+                const uint4 o = load_vec_general<0>(c.old_base, c.pc, k);
+                const uint4 n = load_vec_general<NEW_F32>(c.new_base, c.pc, k);
+                cnt += __popc(nz16_mask(xor4(o, n)));
+            }
         }
         const uint32_t wave_cnt = (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(cnt), 63);
         __syncthreads();                               // earlier readers of s_count_only are done
@@ -1024,6 +1052,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
 
         // ---- (d) the next tile's loads go out now and stay in flight during everything below ----
         int32_t next = -1;
+        const int32_t ticket_before = walk.ticket;
         int next_state = walk_step(a, walk, &next);     // kWalkNeedTicket: decided after the barrier
         next_state = __builtin_amdgcn_readfirstlane(next_state);   // uniform anyway: scalar branches below
         next = __builtin_amdgcn_readfirstlane(next);
@@ -1073,7 +1102,20 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
             settle_ticket();
         // A same-group ticket has just been accepted: nothing may wait now.  This tile is not
         // parked; it is walked again after the count-only pass at the end of the iteration.
-        const bool skip = walk.careful;
+        // Tiles so dense that the ring does not hold a ticket's worth (fewer tiles are parked than a
+        // ticket has, and there is no room for this one), with tiles of the current ticket still
+        // uncounted: waiting now would make every worker of a later group wait for those counts
+        // while this one waits for the prefix of the same ticket's first tile, and the groups of
+        // workers would take turns instead of running side by side.  So the rest of the ticket is
+        // counted first and the ticket's tiles, this one included, are walked again without
+        // publishing, exactly as for a same-group pair (below).
+        bool dense = false;
+#if ROSE_COUNT_AHEAD
+        if (__builtin_expect(ring_used + tile_total > (uint32_t)kRing && q_len < kBatch, 0))
+            dense = !walk.careful && !cur_redo && !walk.redo && !big && next_state == kWalkTile &&
+                    walk.ticket == ticket_before;      // the next tile is of the same ticket: not all of it is counted
+#endif
+        const bool skip = walk.careful || dense;
         if (skip) {
         } else if (big) {
             if (q_len > 0) drain(true);
@@ -1223,26 +1265,34 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         bool late = false;
         bool redo_cur = skip;                          // this iteration's tile was not parked
         for (;;) {
-            if (walk.careful) {
+            if (walk.careful || dense) {
                 // the ticket in use (tA) and the one just accepted (tB) are of one group: publish
-                // the counts of everything not yet published, then walk those tiles again
+                // the counts of everything not yet published, then walk those tiles again.  The
+                // dense case (above) is the same with no second ticket: the rest of tA is counted
+                // and tA is walked again from this iteration's tile on.
+                const bool pair = walk.careful;
                 const int32_t tA = walk.ticket, tB = walk.next_ticket;
+                const int32_t j_end = pair ? 2 * kBatch : kBatch;
                 int32_t j_from = kBatch;               // first slot of tA to walk again
                 if (redo_cur)
                     for (int32_t j = 0; j < kBatch; ++j)
                         if (ticket_tile(a, tA, j) == tile) j_from = j;
                 redo_cur = false;
+                // slot j_from itself is published (it is this iteration's tile); when tA is used up
+                // (j_from = kBatch) every slot of tB is still to be counted
 #pragma unroll 1
-                for (int32_t j = j_from + 1; j < 2 * kBatch; ++j) {
+                for (int32_t j = j_from < kBatch ? j_from + 1 : kBatch; j < j_end; ++j) {
                     const int32_t t = j < kBatch ? ticket_tile(a, tA, j) : ticket_tile(a, tB, j - kBatch);
                     if (t >= 0) publish_count(t);
                 }
                 __syncthreads();
-                if (threadIdx.x == 0)                  // diagnostic word: how often this happened
-                    __hip_atomic_fetch_add(a.abort_flag + kWsCarefulWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (threadIdx.x == 0)                  // diagnostic words: how often each happened
+                    __hip_atomic_fetch_add(a.abort_flag + (pair ? kWsCarefulWord : kWsAheadWord), 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
                 walk.careful = false;
+                dense = false;
                 walk.redo = true;
-                walk.redo_through = tB;
+                walk.redo_through = pair ? tB : tA;
                 walk.j = j_from - 1;
                 next_state = walk_step(a, walk, &next);
                 late = true;

@@ -99,6 +99,7 @@ constexpr int kBatch = ROSE_BATCH;
 
 constexpr size_t kWsAbortOff = 0;
 constexpr int kWsCarefulWord = 2;      // 32-bit word 2 of the header counts same-group ticket pairs (diagnostic)
+constexpr int kWsAheadWord = 3;        // 32-bit word 3: how often tiles were counted ahead of a wait (diagnostic)
 constexpr size_t kWsTicketOff = 4096;
 constexpr size_t kWsHeaderBytes = 8192;
 

@@ -153,6 +153,20 @@ def test_few_workers_dense_changes(monkeypatch):
     assert pairs > 0, "the pair handling never ran: the test does not reach what it is for"
 
 
+@pytest.mark.parametrize("p", [0.45, 0.8, 1.0])
+def test_dense_tiles_are_counted_ahead(p):
+    """More than a third of the elements change: the ring does not hold a ticket's three tiles, and a
+    workgroup counts the rest of its ticket before it waits for room (word 3 of the workspace header
+    counts how often).  Same buckets as ever."""
+    print("case: dense tiles p=%g" % p, flush=True)
+    ts = models.decoder(2, 1024, 16, 16, 64, 2816, 4096, fused=True)
+    c = bern_case(ts, 4, p, seed=77)
+    full_parity(c, check_dense=False)
+    n = int(c.ws.view(torch.int32)[3])
+    print("  tickets counted ahead: %d" % n, flush=True)
+    assert n > 0, "the count-ahead path never ran: the test does not reach what it is for"
+
+
 def test_capacity_overflow_is_reported_and_bounded():
     print("case: capacity overflow", flush=True)
     ts = [T(64, 512, R.SPLIT_ROWS), T(1, 3000, R.REPLICATED)]
