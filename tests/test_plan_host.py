@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2605_06534_amd as R
@@ -194,3 +195,32 @@ def test_pp_stage_helper_partitions_the_model():
     assert models.pp_stage(ts, 8, 4, 0)[0][1]["name"] == "embed"
     assert models.pp_stage(ts, 8, 4, 3)[-1][1]["name"] == "lm_head"
     assert models.numel(models.decoder_8b()) == 8190726144
+
+
+def test_planner_matches_oracle_map_on_random_parameter_sets():
+    """The parameter sets of the GPU sweep (random rules, odd widths, empty tensors, several tiles),
+    on the host: every element's destination and local index from the planner's tables against the
+    oracle's shard map, and the sizes the plan reports against the oracle's."""
+    from test_gpu_random_shapes import random_tensors
+    rng0 = np.random.default_rng(7)
+    for seed in range(40):
+        rng = np.random.default_rng(1000 + seed)
+        tp = int(rng.choice([1, 2, 3, 4, 8]))
+        ts = random_tensors(rng, tp)
+        plan = R.shard_plan(ts, tp)
+        cap = [0] * tp
+        for i, t in enumerate(ts):
+            n = t["rows"] * t["cols"]
+            assert plan.src_numel(i) == n
+            for d in range(tp):
+                assert plan.local_numel(i, d) == oracle.local_numel(t["rule"], t["rows"], t["cols"], tp)
+                cap[d] += oracle.local_numel(t["rule"], t["rows"], t["cols"], tp)
+            if n == 0:
+                continue
+            picks = np.unique(np.concatenate([[0, n - 1], rng0.integers(0, n, 300)]))
+            for g in picks:
+                want = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], tp, int(g) // t["cols"],
+                                        int(g) % t["cols"])
+                assert plan.map_index(i, int(g)) == want, (seed, i, int(g))
+        for d in range(tp):
+            assert plan.bucket_capacity(d) == cap[d]
