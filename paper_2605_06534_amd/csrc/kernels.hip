@@ -750,7 +750,8 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                         const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
                         uint32_t local = base + (ARITH ? (entry >> 16) & (uint32_t)(kTile - 1) : entry >> 16);
                         if (piece >= 0) {              // base is the tile's first element number here
-                            const uint32_t q = __umulhi(local, l_magic) >> l_shift;
+                            // (runs of one element have no magic divisor: the quotient is the number itself)
+                            const uint32_t q = l_run == 1u ? local : (__umulhi(local, l_magic) >> l_shift);
                             local = l_base + q * l_stride + (local - q * l_run);
                         }
                         if constexpr (ARITH) local |= entry & 0x80000000u;

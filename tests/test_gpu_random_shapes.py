@@ -44,3 +44,19 @@ def test_random_parameter_sets(seed):
     full_parity(bern_case(ts, tp, p, seed=seed))
     flags = R.ENCODE_ARITH | (R.ENCODE_REFRESH if seed % 2 else 0)
     check_arith(any_case(ts, tp, p, seed=seed + 500), flags=flags, objects=(seed % 3 == 0))
+
+
+@pytest.mark.parametrize("seed", [278] + list(range(24)))
+def test_random_parameter_sets_from_sharded_senders(seed):
+    """The same kind of random sets, sent by every sender of a random degree to a random destination
+    degree (seed 278: one column per sender and row, found by a longer run of this sweep)."""
+    import math
+    from test_gpu_src_sharding import run
+    rng = np.random.default_rng(5000 + seed)
+    tp = int(rng.choice([1, 2, 3, 4, 8]))
+    tp_src = int(rng.choice([1, 2, 3, 4, 6, 8]))
+    ts = random_tensors(rng, tp * tp_src // math.gcd(tp, tp_src))
+    p = [0.003, 0.05, 0.3, 1.0][seed % 4]
+    print("case: random set from senders seed=%d tp_src=%d tp=%d p=%g shapes=%s" %
+          (seed, tp_src, tp, p, [(t["rows"], t["cols"], t["rule"], t["sections"]) for t in ts]), flush=True)
+    run(ts, tp, tp_src, p, seed)

@@ -96,6 +96,18 @@ def test_full_width_training_to_rollout_8b_layer():
     run(ts, 1, 4, 0.02, seed=4)
 
 
+@pytest.mark.parametrize("tp_src,tp", [(3, 1), (6, 2), (6, 3), (2, 1), (1, 3)])
+def test_pieces_of_a_single_column(tp_src, tp):
+    """Column splits so fine that a sender (or a destination) holds one column per row: runs of one
+    element, for which the kernel's index arithmetic has no magic divisor."""
+    print("case: single-column pieces tp_src=%d tp=%d" % (tp_src, tp), flush=True)
+    ts = [dict(name="c6", rows=25, cols=6, rule=R.SPLIT_COLS, sections=None),
+          dict(name="c6b", rows=3000, cols=6, rule=R.SPLIT_COLS, sections=None),
+          dict(name="r", rows=6, cols=5, rule=R.SPLIT_ROWS, sections=None),
+          dict(name="n", rows=1, cols=77, rule=R.REPLICATED, sections=None)]
+    run(ts, tp, tp_src, 0.3, seed=10 * tp_src + tp)
+
+
 @pytest.mark.parametrize("tp_src,tp", [(1, 4), (4, 4), (8, 4), (2, 8), (4, 1)])
 def test_group_interleaved_qkv_from_the_training_side(tp_src, tp):
     """Fused QKV kept interleaved by KV-head group on the sender side (built with numpy), plainly
