@@ -1376,6 +1376,11 @@ __global__ __launch_bounds__(256) void refresh_replicated_kernel(const int32_t *
 #define ROSE_APPLY_NT 14     // non-temporal hints: 1 entry loads, 2 line loads, 4 line stores, 8 direct stores
                              // (measured best on the 7B workload at 1 - 10 % density)
 #endif
+#ifndef ROSE_APPLY_BLOCKS
+#define ROSE_APPLY_BLOCKS (256 * 128)           // most workgroups an apply launch uses (7B workload, four shards:
+                                                // 2.33 / 5.01 ms at 1 / 5 % against 2.41 / 5.17 ms with 256 * 32;
+                                                // one workgroup per 256 entries is slower again at 10 %)
+#endif
 constexpr int kApplyThreads = 256;
 constexpr int kApplyWaves = kApplyThreads / 64;
 #ifndef ROSE_APPLY_LINE
@@ -1819,7 +1824,7 @@ int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_num
                  int arith, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = (b.capacity + kApplyThreads - 1) / kApplyThreads;
-    int blocks = chunks < 1 ? 1 : (chunks > 256 * 32 ? 256 * 32 : (int)chunks);
+    int blocks = chunks < 1 ? 1 : (chunks > ROSE_APPLY_BLOCKS ? ROSE_APPLY_BLOCKS : (int)chunks);
     hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs, arith);
     return (int)hipGetLastError();
 }
@@ -1837,7 +1842,7 @@ int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tenso
                         void *const *dst_ptrs, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = ((int64_t)(object_bytes / 6) + kApplyThreads - 1) / kApplyThreads;
-    int blocks = chunks < 1 ? 1 : (chunks > 256 * 32 ? 256 * 32 : (int)chunks);
+    int blocks = chunks < 1 ? 1 : (chunks > ROSE_APPLY_BLOCKS ? ROSE_APPLY_BLOCKS : (int)chunks);
     hipLaunchKernelGGL(apply_object_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, static_cast<const char *>(object),
                        object_bytes, n_tensors, local_numel, dst_ptrs);
     return (int)hipGetLastError();
