@@ -57,6 +57,8 @@ def _load():
         lib.orc_encode_tensor_src.argtypes = [vp, vp, i32, i32, i64, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp]
         lib.orc_apply.restype = i32
         lib.orc_apply.argtypes = [vp, vp, i64, vp, i64]
+        lib.orc_stage_of.restype = i32
+        lib.orc_stage_of.argtypes = [i32, i32, i32]
         u16 = ctypes.c_uint16
         lib.orc_bf16_nearest.restype = u16
         lib.orc_bf16_nearest.argtypes = [ctypes.c_double]
@@ -193,6 +195,47 @@ def encode_model(tensors, tp):
         idx = np.concatenate([segs[d][0] for segs in per_tensor]) if tensors else np.empty(0, np.int32)
         val = np.concatenate([segs[d][1] for segs in per_tensor]) if tensors else np.empty(0, np.uint16)
         buckets.append({"idx": idx, "val": val, "seg_off": seg_off})
+    return buckets
+
+
+LAYER_FIRST, LAYER_LAST = -1, -2
+
+
+def stage_of(layer, n_layers, pp):
+    """Pipeline stage (of pp) that holds a tensor of decoder layer `layer` (LAYER_FIRST: in front of
+    the layers, LAYER_LAST: behind them)."""
+    s = _load().orc_stage_of(int(layer), int(n_layers), int(pp))
+    if s < 0:
+        raise OracleError("stage_of(%d, %d, %d)" % (layer, n_layers, pp))
+    return s
+
+
+def encode_model_pp(tensors, tp, tp_src, src_rank, n_layers, pp_src, stage_src, pp_dst):
+    """Dense-to-sparse by the sender that is rank `src_rank` of `tp_src` in pipeline stage `stage_src`
+    of `pp_src`, towards `pp_dst` receiving stages of `tp` shards each.  `tensors` lists the whole
+    model (each with "layer"); "old" / "new" are the sender's slices and are looked at only for
+    tensors of its own stage.  -> pp_dst * tp buckets, bucket stage * tp + d for shard d of a
+    receiving stage; every bucket's seg_off counts all tensors of the model (segments of tensors that
+    the sender does not hold, or that belong to another receiving stage, are empty)."""
+    empty = (np.empty(0, np.int32), np.empty(0, np.uint16))
+    per = []                                           # per tensor: receiving stage, per-shard (idx, val)
+    for i, t in enumerate(tensors):
+        to = stage_of(t["layer"], n_layers, pp_dst)
+        if stage_of(t["layer"], n_layers, pp_src) != stage_src:
+            per.append((to, [empty] * tp))
+            continue
+        per.append((to, encode_tensor_src(t["old"], t["new"], t["rows"], t["cols"], t["rule"], t.get("sections"),
+                                          tp, tp_src, src_rank, sends_replicated=(i % tp_src == src_rank),
+                                          src_groups=t.get("src_groups") or 0)))
+    buckets = []
+    for stage in range(pp_dst):
+        for d in range(tp):
+            segs = [s[d] if to == stage else empty for to, s in per]
+            seg_off = np.zeros(len(tensors) + 1, dtype=np.int64)
+            seg_off[1:] = np.cumsum([a.size for a, _ in segs])
+            buckets.append({"idx": np.concatenate([a for a, _ in segs]) if segs else empty[0],
+                            "val": np.concatenate([v for _, v in segs]) if segs else empty[1],
+                            "seg_off": seg_off})
     return buckets
 
 

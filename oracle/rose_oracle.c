@@ -28,7 +28,8 @@
  *
  * Parity pins live in tests/ (numpy flatnonzero for TP=1, numpy slicing for
  * the shard map, round-trip and counting invariants, torch's CPU cast for
- * round-to-nearest-even).  No function here is "parity unpinned".
+ * round-to-nearest-even, hand-written stage tables for the pipeline split).
+ * No function here is "parity unpinned".
  */
 #include <stdint.h>
 #include <stddef.h>
@@ -283,6 +284,28 @@ int orc_encode_tensor_src(const uint16_t *old_slice, const void *new_slice, int 
         }
     }
     return ORC_OK;
+}
+
+/*
+ * Pipeline stages (Sec. 4.2, "Shard-aware Weight Transfer": tensor AND pipeline
+ * parallelism on both sides, e.g. TP8 x PP2 feeding TP4).  The paper names no
+ * split; the reading taken is the uniform one: the n_layers decoder layers go
+ * to the pp stages in consecutive groups of n_layers / pp, the tensors in
+ * front of the layers (layer = ORC_LAYER_FIRST: the embedding) stay with the
+ * first stage and those behind them (ORC_LAYER_LAST: final norm, head) with
+ * the last.  Returns the stage, or -1 for arguments outside that reading.
+ */
+enum { ORC_LAYER_FIRST = -1, ORC_LAYER_LAST = -2 };
+int orc_stage_of(int layer, int n_layers, int pp)
+{
+    if (pp < 1) return -1;
+    if (layer == ORC_LAYER_FIRST) return 0;
+    if (layer == ORC_LAYER_LAST) return pp - 1;
+    if (n_layers < 1 || n_layers % pp != 0 || layer < 0 || layer >= n_layers) return -1;
+    int group = n_layers / pp;
+    for (int stage = 0; stage < pp; ++stage)         /* the group whose layer range holds `layer` */
+        if (stage * group <= layer && layer < (stage + 1) * group) return stage;
+    return -1;
 }
 
 /*

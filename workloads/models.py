@@ -1,7 +1,9 @@
 """Tensor lists (shapes + shard rules) of the synthetic parameter sets.
 
 Shapes only: no arithmetic of the method lives here.  A tensor descriptor is a
-dict ``{"name", "rows", "cols", "rule", "sections"}``; rules are the interface
+dict ``{"name", "rows", "cols", "rule", "sections", "layer"}`` (layer: the decoder layer the
+tensor belongs to, -1 for what stands in front of the layers, -2 for what stands behind them;
+it matters to pipeline-parallel plans only); rules are the interface
 values 0 replicated, 1 split rows (dim 0), 2 split cols (dim 1), 3 fused rows
 (dim 0 is a stack of sections, each split).  The layouts are the usual
 tensor-parallel ones for a dense decoder: QKV / gate / up are column-parallel
@@ -13,34 +15,37 @@ norm weights are replicated.
 REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
 
 
-def _t(name, rows, cols, rule, sections=None):
+LAYER_FIRST, LAYER_LAST = -1, -2
+
+
+def _t(name, rows, cols, rule, sections=None, layer=0):
     return {"name": name, "rows": int(rows), "cols": int(cols), "rule": rule,
-            "sections": [int(s) for s in sections] if sections else None}
+            "sections": [int(s) for s in sections] if sections else None, "layer": int(layer)}
 
 
 def decoder(layers, hidden, q_heads, kv_heads, head_dim, inter, vocab, fused=True):
     """Dense decoder parameter set, untied embedding / lm_head, RMSNorm weights."""
     q, kv = q_heads * head_dim, kv_heads * head_dim
-    ts = [_t("embed", vocab, hidden, SPLIT_ROWS)]
+    ts = [_t("embed", vocab, hidden, SPLIT_ROWS, layer=LAYER_FIRST)]
     for i in range(layers):
         p = "l%d." % i
-        ts.append(_t(p + "input_norm", 1, hidden, REPLICATED))
+        ts.append(_t(p + "input_norm", 1, hidden, REPLICATED, layer=i))
         if fused:
-            ts.append(_t(p + "qkv", q + 2 * kv, hidden, FUSED_ROWS, [q, kv, kv]))
+            ts.append(_t(p + "qkv", q + 2 * kv, hidden, FUSED_ROWS, [q, kv, kv], layer=i))
         else:
-            ts.append(_t(p + "q", q, hidden, SPLIT_ROWS))
-            ts.append(_t(p + "k", kv, hidden, SPLIT_ROWS))
-            ts.append(_t(p + "v", kv, hidden, SPLIT_ROWS))
-        ts.append(_t(p + "o", hidden, q, SPLIT_COLS))
-        ts.append(_t(p + "post_norm", 1, hidden, REPLICATED))
+            ts.append(_t(p + "q", q, hidden, SPLIT_ROWS, layer=i))
+            ts.append(_t(p + "k", kv, hidden, SPLIT_ROWS, layer=i))
+            ts.append(_t(p + "v", kv, hidden, SPLIT_ROWS, layer=i))
+        ts.append(_t(p + "o", hidden, q, SPLIT_COLS, layer=i))
+        ts.append(_t(p + "post_norm", 1, hidden, REPLICATED, layer=i))
         if fused:
-            ts.append(_t(p + "gate_up", 2 * inter, hidden, FUSED_ROWS, [inter, inter]))
+            ts.append(_t(p + "gate_up", 2 * inter, hidden, FUSED_ROWS, [inter, inter], layer=i))
         else:
-            ts.append(_t(p + "gate", inter, hidden, SPLIT_ROWS))
-            ts.append(_t(p + "up", inter, hidden, SPLIT_ROWS))
-        ts.append(_t(p + "down", hidden, inter, SPLIT_COLS))
-    ts.append(_t("final_norm", 1, hidden, REPLICATED))
-    ts.append(_t("lm_head", vocab, hidden, SPLIT_ROWS))
+            ts.append(_t(p + "gate", inter, hidden, SPLIT_ROWS, layer=i))
+            ts.append(_t(p + "up", inter, hidden, SPLIT_ROWS, layer=i))
+        ts.append(_t(p + "down", hidden, inter, SPLIT_COLS, layer=i))
+    ts.append(_t("final_norm", 1, hidden, REPLICATED, layer=LAYER_LAST))
+    ts.append(_t("lm_head", vocab, hidden, SPLIT_ROWS, layer=LAYER_LAST))
     return ts
 
 
