@@ -16,9 +16,14 @@
  *     valid until the work queued on `stream` has finished.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     encode / apply / dense_copy / bw_probe only queue work and return; they do
- *     not synchronise and do not allocate after the plan's first use on a device.
+ *     not synchronise and do not allocate after the plan's first use on a device
+ *     (rose_plan_upload makes that first use explicit).
+ *   - A plan is used on ONE device: the first device call on it (or rose_plan_upload)
+ *     binds it to the device that is current then; on any other device the calls
+ *     return ROSE_ERR_ARG.  Make one plan per device.
  *   - Errors that the host can see are returned before anything is queued.
- *     No exception crosses this boundary and there is no global state.
+ *     No exception crosses this boundary.  The library keeps no state outside plan
+ *     handles.
  *   - Weights are 16-bit patterns (bf16).  "Changed" means the two patterns
  *     differ; an entry carries the new pattern and applying it overwrites.
  *   - Entry coordinates are int32 flat indices local to the destination shard's
@@ -76,8 +81,13 @@ typedef struct {
                                                       split that layout in tp_src equal row blocks (whole
                                                       groups).  Every section and tp_src must divide by G
                                                       resp. into it. */
-    int32_t reserved;                              /* 0 */
+    int32_t layer;                                 /* pipeline plans (rose_shard_plan_create_pp) only: decoder layer
+                                                      0 .. n_layers-1 the tensor belongs to, ROSE_LAYER_FIRST for
+                                                      tensors in front of the layers (embedding), ROSE_LAYER_LAST
+                                                      for those behind them (final norm, head); ignored otherwise */
 } rose_tensor_desc;
+#define ROSE_LAYER_FIRST (-1)
+#define ROSE_LAYER_LAST (-2)
 
 typedef struct rose_plan rose_plan;
 
@@ -116,18 +126,67 @@ rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, int32_t n_te
  * destination shard of degree tp_src).  Each element goes to the destination shard that holds it,
  * at that shard's local index; a destination is only reached where the two slice ranges overlap.
  * A replicated tensor is held by every sender and sent by exactly one: sender (ordinal mod
- * tp_src); the others' pointers for it are not read.  The tp_src senders' buckets for one
+ * tp_src); the others' pointers for it are not read by rose_delta_encode (with ROSE_ENCODE_REFRESH
+ * they are: every sender refreshes its own copy; rose_plan_tensor_is_read tells).  The tp_src senders' buckets for one
  * destination are disjoint and may be applied in any order.  tp_src = 1, src_rank = 0 is
  * rose_shard_plan_create.  rose_dense_copy with such a plan copies the part of the destination
  * shard that the sender holds.  Errors as above; both degrees must divide the split dimensions.
  */
 rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
                                        int32_t tp_src, int32_t src_rank, rose_plan **out);
+/*
+ * The same with pipeline stages on both sides (Sec. 4.2 "Shard-aware Weight Transfer": TP and PP on the
+ * training and on the serving side, e.g. TP 8 x PP 2 feeding TP 4).  `tensors` lists the WHOLE model in
+ * one order that every sender and receiver shares, each tensor naming its layer; a side with pp stages
+ * deals the n_layers layers to them in equal consecutive groups (pp must divide n_layers), ROSE_LAYER_FIRST
+ * tensors go with stage 0, ROSE_LAYER_LAST tensors with the last stage.
+ *   sender    rank src_rank of tp_src in stage stage_src of pp_src: it holds (and encode reads) only the
+ *             tensors of its stage; the pointer-table entries of all other tensors are never read.
+ *   receiver  pp_dst stages of tp shards each.  There are tp * pp_dst buckets (at most ROSE_MAX_TP):
+ *             bucket b = stage * tp + shard receives the tensors of that stage.  Wherever this header says
+ *             "shard d" of a plan (rose_delta_encode's bucket array, rose_delta_apply, rose_dense_copy,
+ *             rose_bucket_pack, an object's shard word, the queries), a pipeline plan takes the bucket number.
+ * Tensor numbers stay model-wide everywhere: seg_off has n_tensors + 1 entries in every bucket (segments
+ * of tensors that the bucket's stage does not hold are empty), a receiver's dst_ptrs table has
+ * n_tensors entries of which only its own stage's are read, and a transport object carries the
+ * model-wide segment table, so a receiver whose stage split differs from the sender's places every
+ * entry by (tensor number, local index) alone.  rose_plan_local_numel is 0 for a tensor the bucket's
+ * stage does not hold, rose_plan_src_numel is 0 for one the sender does not hold.
+ * pp_src = pp_dst = 1 is rose_shard_plan_create_src.  Errors as above; ROSE_ERR_SHAPE if a pp does not
+ * divide n_layers, ROSE_ERR_ARG for a layer outside 0 .. n_layers-1, ROSE_ERR_UNSUPPORTED if tp * pp_dst
+ * exceeds ROSE_MAX_TP.
+ */
+rose_status rose_shard_plan_create_pp(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
+                                      int32_t tp_src, int32_t src_rank, int32_t n_layers, int32_t pp_src,
+                                      int32_t stage_src, int32_t pp_dst, rose_plan **out);
 void rose_shard_plan_destroy(rose_plan *plan);
+/*
+ * Makes the plan resident on the current device (HOST call; allocates and copies the plan's tables,
+ * asks the runtime how many workgroups of each kernel fit) and
+ * binds the plan to that device.  The other device calls do this by themselves on first use; call it
+ * ahead of time where a later call must not allocate (graph capture).
+ * Idempotent.  ROSE_ERR_HIP if the runtime fails, ROSE_ERR_ARG if the plan is bound to another device.
+ */
+rose_status rose_plan_upload(const rose_plan *plan);
+/*
+ * Caps the number of workgroups of later encode launches with this plan that walk tiles, e.g. to
+ * leave compute units to other kernels (0 = no cap, the default; values of 64 or less, or above what
+ * the device holds, are ignored).  May be called at any time from any thread; a launch uses the value
+ * it finds.
+ */
+rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
 
 /* Host queries on a plan (no GPU needed). */
 int32_t rose_plan_n_tensors(const rose_plan *plan);
 int32_t rose_plan_tp(const rose_plan *plan);
+/* number of buckets: tp, or tp * pp_dst for a pipeline plan */
+int32_t rose_plan_n_buckets(const rose_plan *plan);
+/* stage that holds tensor t on the sending and on the receiving side (each may be NULL) */
+rose_status rose_plan_stage_of(const rose_plan *plan, int32_t t, int32_t *stage_src, int32_t *stage_dst);
+/* *is_read = 1 if an encode launch with these flags (ROSE_ENCODE_*) dereferences entry t of old_ptrs and
+ * new_ptrs: the sender holds the tensor, it is not empty, and the sender sends it or (ROSE_ENCODE_REFRESH)
+ * refreshes it.  Entries with 0 may hold anything. */
+rose_status rose_plan_tensor_is_read(const rose_plan *plan, int32_t t, uint32_t flags, int32_t *is_read);
 /* elements of the model before tensor t (int64 model-wide position of its element 0) */
 rose_status rose_plan_tensor_base(const rose_plan *plan, int32_t t, int64_t *global_base);
 /* elements of shard d's local copy of tensor t */
@@ -170,10 +229,8 @@ rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
  * (different streams, different workspaces) can starve each other until the bounded wait gives up:
  * order encode launches of one device on one stream.
  *
- * Environment: ROSE_ENCODE_WORKERS=<n> (read at every call) caps the number of workgroups that
- * walk tiles, e.g. to leave compute units to other kernels; values of 64 or less, or above what
- * the device holds, are ignored.  After a launch the 32-bit words 2 and 3 of the workspace hold
- * diagnostic counts (how often a workgroup received two tickets of one group of blocks in a row;
+ * rose_plan_set_worker_cap limits the workgroups that walk tiles.  After a launch the 32-bit words 2
+ * and 3 of the workspace hold diagnostic counts (how often a workgroup received two tickets of one group of blocks in a row;
  * how often it counted a ticket's remaining tiles ahead of a wait, which happens where more than
  * about a third of the elements change).
  */
@@ -188,7 +245,9 @@ rose_status rose_delta_encode(const rose_plan *plan, const void *const *old_ptrs
  * tensor the sender holds equals the new one as bf16 (for fp32 input: its round-to-nearest-even
  * cast), so that the same old tensors serve the next step while the new ones may be overwritten by
  * the trainer.  Only the 16-byte vectors that contain a change are written (whole replicated
- * tensors, which are small, are copied by a second kernel once every destination has read them).
+ * tensors, which are small, are copied by a second kernel once every destination has read them;
+ * that includes the replicated tensors a sender holds without sending them, so their old and new
+ * pointers must be valid here although rose_delta_encode never reads them).
  * old_ptrs' tensors are WRITTEN; everything else as rose_delta_encode.  If the launch gives up
  * (see above) or a bucket overflows, old is already partly refreshed and the dropped entries
  * cannot be produced again from it: size buckets for the worst case when using this call, or
@@ -280,10 +339,16 @@ rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, 
  *                     object_bytes is too small); the range is checked against the bucket's true
  *                     total on the device: a range beyond it yields an object with a zero magic,
  *                     which nobody applies.
- * rose_object_apply   checks the header on the device (magic, version, T, sizes against
- *                     object_bytes, segment table ends) and applies the entries to the shard's
- *                     tensors; an object that fails the check changes nothing.  Same rule as
- *                     rose_delta_apply about concurrent writers of the destination.
+ * rose_object_apply   checks the object on the device and applies the entries to the shard's
+ *                     tensors; an object that fails the check changes nothing.  Checked: the header
+ *                     (magic, version, shard, T, sizes against object_bytes), the segment table (starts
+ *                     at 0, never decreases, ends at n) and, in a pass over all indices, that they
+ *                     ascend strictly inside every segment (the apply kernel's ownership of 64-byte
+ *                     pieces relies on that order; an index outside its tensor is dropped as in
+ *                     rose_delta_apply).  The verdict travels through one of 4096 words of the plan's
+ *                     device memory, taken in turn: more than 4096 object applies of one plan in
+ *                     flight at once may take each other's verdicts.  Same rule as rose_delta_apply
+ *                     about concurrent writers of the destination.
  * rose_object_check   synchronises `stream`, reads the header back and returns ROSE_ERR_ARG for a
  *                     malformed object; shard / first_entry / n_entries / payload kind (host, each
  *                     may be NULL).

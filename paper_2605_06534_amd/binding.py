@@ -15,6 +15,7 @@ ROSE_MAX_SECTIONS = 4
 REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
 BF16, FP32_RNE = 0, 1
 OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED = range(7)
+LAYER_FIRST, LAYER_LAST = -1, -2
 
 _LIB_PATH = os.environ.get("ROSE_DELTA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
                                                             "librose_delta.so")
@@ -26,7 +27,7 @@ if not os.path.exists(_LIB_PATH):
 class TensorDesc(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("rule", ctypes.c_int32),
                 ("n_sections", ctypes.c_int32), ("section_rows", ctypes.c_int64 * ROSE_MAX_SECTIONS),
-                ("src_groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("src_groups", ctypes.c_int32), ("layer", ctypes.c_int32)]
 
 
 class CBucket(ctypes.Structure):
@@ -39,9 +40,15 @@ _P = ctypes.POINTER
 _SIGS = {
     "rose_shard_plan_create": (_i32, [_P(TensorDesc), _i32, _i32, _P(_vp)]),
     "rose_shard_plan_create_src": (_i32, [_P(TensorDesc), _i32, _i32, _i32, _i32, _P(_vp)]),
+    "rose_shard_plan_create_pp": (_i32, [_P(TensorDesc), _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _P(_vp)]),
     "rose_shard_plan_destroy": (None, [_vp]),
+    "rose_plan_upload": (_i32, [_vp]),
+    "rose_plan_set_worker_cap": (_i32, [_vp, _i32]),
     "rose_plan_n_tensors": (_i32, [_vp]),
     "rose_plan_tp": (_i32, [_vp]),
+    "rose_plan_n_buckets": (_i32, [_vp]),
+    "rose_plan_stage_of": (_i32, [_vp, _i32, _P(_i32), _P(_i32)]),
+    "rose_plan_tensor_is_read": (_i32, [_vp, _i32, ctypes.c_uint32, _P(_i32)]),
     "rose_plan_tensor_base": (_i32, [_vp, _i32, _P(_i64)]),
     "rose_plan_local_numel": (_i32, [_vp, _i32, _i32, _P(_i64)]),
     "rose_plan_src_numel": (_i32, [_vp, _i32, _P(_i64)]),
@@ -105,8 +112,10 @@ class Plan:
         self.tensors = tensors
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            _lib.rose_shard_plan_destroy(self._h)
+        # at interpreter shutdown the module's globals may be gone already: then the process's end frees the plan
+        h, lib = getattr(self, "_h", None), globals().get("_lib")
+        if h and lib is not None:
+            lib.rose_shard_plan_destroy(h)
             self._h = None
 
     @property
@@ -116,6 +125,26 @@ class Plan:
     @property
     def tp(self):
         return _lib.rose_plan_tp(self._h)
+
+    @property
+    def n_buckets(self):
+        return _lib.rose_plan_n_buckets(self._h)
+
+    def upload(self):
+        _check(_lib.rose_plan_upload(self._h), "plan_upload")
+
+    def set_worker_cap(self, workers):
+        _check(_lib.rose_plan_set_worker_cap(self._h, workers), "plan_set_worker_cap")
+
+    def stage_of(self, t):
+        a, b = _i32(), _i32()
+        _check(_lib.rose_plan_stage_of(self._h, t, ctypes.byref(a), ctypes.byref(b)), "plan_stage_of")
+        return a.value, b.value
+
+    def tensor_is_read(self, t, flags=0):
+        v = _i32()
+        _check(_lib.rose_plan_tensor_is_read(self._h, t, flags, ctypes.byref(v)), "plan_tensor_is_read")
+        return bool(v.value)
 
     def tensor_base(self, t):
         v = _i64()
@@ -154,9 +183,11 @@ class Plan:
         return v.value
 
 
-def shard_plan(tensors, tp, tp_src=1, src_rank=0):
+def shard_plan(tensors, tp, tp_src=1, src_rank=0, n_layers=0, pp_src=1, stage_src=0, pp_dst=1):
     """tensors: list of dicts with rows, cols, rule and (fused rows) sections.  With tp_src > 1 the
-    plan is for the sender that holds shard src_rank of tp_src of every tensor."""
+    plan is for the sender that holds shard src_rank of tp_src of every tensor; with pp_src / pp_dst
+    > 1 (each tensor then names its "layer") for the sender in stage stage_src of pp_src feeding
+    pp_dst stages of tp shards."""
     arr = (TensorDesc * max(len(tensors), 1))()
     for i, t in enumerate(tensors):
         arr[i].rows, arr[i].cols, arr[i].rule = t["rows"], t["cols"], t["rule"]
@@ -167,8 +198,12 @@ def shard_plan(tensors, tp, tp_src=1, src_rank=0):
         for j, s in enumerate(sec):
             arr[i].section_rows[j] = s
         arr[i].src_groups = int(t.get("src_groups") or 0)
+        arr[i].layer = int(t.get("layer") or 0)
     h = _vp()
-    if tp_src == 1 and src_rank == 0:
+    if pp_src != 1 or pp_dst != 1 or stage_src != 0 or n_layers != 0:
+        _check(_lib.rose_shard_plan_create_pp(arr, len(tensors), tp, tp_src, src_rank, n_layers, pp_src, stage_src,
+                                              pp_dst, ctypes.byref(h)), "shard_plan")
+    elif tp_src == 1 and src_rank == 0:
         _check(_lib.rose_shard_plan_create(arr, len(tensors), tp, ctypes.byref(h)), "shard_plan")
     else:
         _check(_lib.rose_shard_plan_create_src(arr, len(tensors), tp, tp_src, src_rank, ctypes.byref(h)), "shard_plan")
@@ -198,7 +233,7 @@ def workspace(plan, device="cuda"):
 
 
 def delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=None):
-    cb = (CBucket * plan.tp)(*[b.c() for b in buckets])
+    cb = (CBucket * plan.n_buckets)(*[b.c() for b in buckets])
     _check(_lib.rose_delta_encode(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, cb,
                                   ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
            "delta_encode")
@@ -206,7 +241,7 @@ def delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=None):
 
 def delta_encode_refresh(plan, old_tab, new_tab, new_dtype, buckets, ws, stream=None):
     """delta_encode that also makes the old tensors equal to the new ones (as bf16)."""
-    cb = (CBucket * plan.tp)(*[b.c() for b in buckets])
+    cb = (CBucket * plan.n_buckets)(*[b.c() for b in buckets])
     _check(_lib.rose_delta_encode_refresh(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, cb,
                                           ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
            "delta_encode_refresh")
@@ -218,7 +253,7 @@ PAYLOAD_NEW, PAYLOAD_ARITH = 0, 1
 
 def delta_encode_ex(plan, old_tab, new_tab, new_dtype, flags, buckets, ws, stream=None):
     """delta_encode with flags: ENCODE_REFRESH (old tensors are written), ENCODE_ARITH (arithmetic payloads)."""
-    cb = (CBucket * plan.tp)(*[b.c() for b in buckets])
+    cb = (CBucket * plan.n_buckets)(*[b.c() for b in buckets])
     _check(_lib.rose_delta_encode_ex(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, flags, cb,
                                      ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
            "delta_encode_ex")

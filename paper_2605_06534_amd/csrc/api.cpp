@@ -11,64 +11,70 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 
 // Copy the piece and tile tables to the current device once; later calls on the same device
 // reuse them.  A plan is bound to the first device it is used on.
-rose_status device_tables(const rose_plan *p, const rose::Piece **pieces, const int32_t **tile_piece,
-                          const int32_t **local_numel = nullptr) {
+rose_status device_tables(const rose_plan *p) {
     std::lock_guard<std::mutex> lock(p->mu);
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return ROSE_ERR_HIP;
-    if (p->device == -1) {
-        rose::Piece *dp = nullptr;
-        int32_t *dt = nullptr, *dn = nullptr;
-        std::vector<int32_t> numel(p->n_tensors);
-        for (int32_t i = 0; i < p->n_tensors; ++i) {
-            const rose_tensor_desc &t = p->tensors[i];
-            numel[i] = (int32_t)(t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : p->tp));
-        }
-        std::vector<int32_t> repl;
-        std::vector<int64_t> repl_numel;
-        for (int32_t i = 0; i < p->n_tensors; ++i) {
-            if (p->tensors[i].rule == ROSE_REPLICATED && p->tensors[i].rows * p->tensors[i].cols > 0) {
-                repl.push_back(i);
-                repl_numel.push_back(p->tensors[i].rows * p->tensors[i].cols);
-            }
-        }
-        int32_t *dr = nullptr;
-        int64_t *drn = nullptr;
-        size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
-        size_t nb = numel.size() * sizeof(int32_t);
-        bool ok = hipMalloc(reinterpret_cast<void **>(&dp), pb) == hipSuccess &&
-                  hipMalloc(reinterpret_cast<void **>(&dt), tb) == hipSuccess &&
-                  hipMalloc(reinterpret_cast<void **>(&dn), nb) == hipSuccess &&
-                  hipMemcpy(dp, p->pieces.data(), pb, hipMemcpyHostToDevice) == hipSuccess &&
-                  hipMemcpy(dt, p->tile_piece.data(), tb, hipMemcpyHostToDevice) == hipSuccess &&
-                  hipMemcpy(dn, numel.data(), nb, hipMemcpyHostToDevice) == hipSuccess;
-        if (ok && !repl.empty()) {
-            ok = hipMalloc(reinterpret_cast<void **>(&dr), repl.size() * sizeof(int32_t)) == hipSuccess &&
-                 hipMalloc(reinterpret_cast<void **>(&drn), repl.size() * sizeof(int64_t)) == hipSuccess &&
-                 hipMemcpy(dr, repl.data(), repl.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
-                 hipMemcpy(drn, repl_numel.data(), repl.size() * sizeof(int64_t), hipMemcpyHostToDevice) == hipSuccess;
-        }
-        if (!ok) {
-            if (dp) (void)hipFree(dp);
-            if (dt) (void)hipFree(dt);
-            if (dn) (void)hipFree(dn);
-            if (dr) (void)hipFree(dr);
-            if (drn) (void)hipFree(drn);
-            return ROSE_ERR_HIP;
-        }
-        p->d_pieces = dp;
-        p->d_tile_piece = dt;
-        p->d_local_numel = dn;
-        p->d_repl_list = dr;
-        p->d_repl_numel = drn;
-        p->n_repl = (int32_t)repl.size();
-        p->device = dev;
-    } else if (p->device != dev) {
-        return ROSE_ERR_ARG;
+    if (p->device == dev) return ROSE_OK;
+    if (p->device != -1) return ROSE_ERR_ARG;
+
+    // elements of a shard's copy of each tensor, per receiving stage (0: the stage does not hold it)
+    std::vector<int32_t> numel((size_t)p->pp_dst * p->n_tensors, 0);
+    for (int32_t i = 0; i < p->n_tensors; ++i) {
+        const rose_tensor_desc &t = p->tensors[i];
+        numel[(size_t)p->stage_dst_of[i] * p->n_tensors + i] =
+            (int32_t)(t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : p->tp));
     }
-    *pieces = p->d_pieces;
-    *tile_piece = p->d_tile_piece;
-    if (local_numel) *local_numel = p->d_local_numel;
+    // replicated tensors the sender holds: a refresh copies them whole, sent from here or not
+    std::vector<int32_t> repl;
+    std::vector<int64_t> repl_numel;
+    for (int32_t i = 0; i < p->n_tensors; ++i) {
+        const rose_tensor_desc &t = p->tensors[i];
+        if (t.rule == ROSE_REPLICATED && t.rows * t.cols > 0 && p->stage_src_of[i] == p->stage_src) {
+            repl.push_back(i);
+            repl_numel.push_back(t.rows * t.cols);
+        }
+    }
+    rose::Piece *dp = nullptr;
+    int32_t *dt = nullptr, *dn = nullptr, *dr = nullptr;
+    int64_t *drn = nullptr;
+    unsigned long long *dv = nullptr;
+    int resident[8];
+    const size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
+    const size_t nb = numel.size() * sizeof(int32_t), vb = kVerdictSlots * sizeof(unsigned long long);
+    bool ok = hipMalloc(reinterpret_cast<void **>(&dp), pb) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&dt), tb) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&dn), nb) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&dv), vb) == hipSuccess &&
+              hipMemcpy(dp, p->pieces.data(), pb, hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(dt, p->tile_piece.data(), tb, hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(dn, numel.data(), nb, hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemset(dv, 0, vb) == hipSuccess;
+    if (ok && !repl.empty()) {
+        ok = hipMalloc(reinterpret_cast<void **>(&dr), repl.size() * sizeof(int32_t)) == hipSuccess &&
+             hipMalloc(reinterpret_cast<void **>(&drn), repl.size() * sizeof(int64_t)) == hipSuccess &&
+             hipMemcpy(dr, repl.data(), repl.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+             hipMemcpy(drn, repl_numel.data(), repl.size() * sizeof(int64_t), hipMemcpyHostToDevice) == hipSuccess;
+    }
+    ok = ok && rose::encode_resident_all(resident) == 0;
+    if (!ok) {
+        if (dp) (void)hipFree(dp);
+        if (dt) (void)hipFree(dt);
+        if (dn) (void)hipFree(dn);
+        if (dv) (void)hipFree(dv);
+        if (dr) (void)hipFree(dr);
+        if (drn) (void)hipFree(drn);
+        return ROSE_ERR_HIP;
+    }
+    p->d_pieces = dp;
+    p->d_tile_piece = dt;
+    p->d_local_numel = dn;
+    p->d_verdict = dv;
+    p->d_repl_list = dr;
+    p->d_repl_numel = drn;
+    p->n_repl = (int32_t)repl.size();
+    std::memcpy(p->resident, resident, sizeof resident);
+    p->device = dev;
     return ROSE_OK;
 }
 
@@ -81,11 +87,17 @@ rose_status check_bucket(const rose_bucket &b) {
 
 }  // namespace
 
+extern "C" rose_status rose_plan_upload(const rose_plan *p) {
+    if (!p) return ROSE_ERR_ARG;
+    return device_tables(p);
+}
+
 extern "C" void rose_shard_plan_destroy(rose_plan *p) {
     if (!p) return;
     if (p->d_pieces) (void)hipFree(p->d_pieces);
     if (p->d_tile_piece) (void)hipFree(p->d_tile_piece);
     if (p->d_local_numel) (void)hipFree(p->d_local_numel);
+    if (p->d_verdict) (void)hipFree(p->d_verdict);
     if (p->d_repl_list) (void)hipFree(p->d_repl_list);
     if (p->d_repl_numel) (void)hipFree(p->d_repl_numel);
     delete p;
@@ -98,11 +110,10 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
     size_t need = 0;
     rose_plan_workspace_bytes(p, &need);
-    if (workspace_bytes < need) return ROSE_ERR_ARG;
-    if (!aligned(workspace, 256) || !aligned(old_ptrs, 8) || !aligned(new_ptrs, 8)) return ROSE_ERR_ALIGN;
+    if (!aligned(old_ptrs, 8) || !aligned(new_ptrs, 8)) return ROSE_ERR_ALIGN;
     rose::EncodeArgs a;
     std::memset(&a, 0, sizeof a);
-    for (int32_t d = 0; d < p->tp; ++d) {
+    for (int32_t d = 0; d < p->n_buckets; ++d) {
         rose_status s = check_bucket(buckets[d]);
         if (s != ROSE_OK) return s;
         a.bucket[d].idx = buckets[d].idx;
@@ -110,10 +121,14 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
         a.bucket[d].capacity = buckets[d].capacity;
         a.bucket[d].seg_off = buckets[d].seg_off;
     }
+    rose_status s = device_tables(p);
+    if (s != ROSE_OK) return s;
+    if (workspace_bytes < need) return ROSE_ERR_ARG;
+    if (!aligned(workspace, 256)) return ROSE_ERR_ALIGN;
     std::memcpy(a.chain_first, p->chain_first, sizeof a.chain_first);
     std::memcpy(a.block_first, p->block_first, sizeof a.block_first);
-    rose_status s = device_tables(p, &a.pieces, &a.tile_piece);
-    if (s != ROSE_OK) return s;
+    a.pieces = p->d_pieces;
+    a.tile_piece = p->d_tile_piece;
     a.old_ptrs = old_ptrs;
     a.new_ptrs = new_ptrs;
     char *ws = static_cast<char *>(workspace);
@@ -121,12 +136,15 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     a.ticket = reinterpret_cast<unsigned int *>(ws + rose::kWsTicketOff);
     a.tile_desc = reinterpret_cast<unsigned long long *>(ws + rose::kWsHeaderBytes);
     a.n_tiles = (int32_t)p->tile_piece.size();
-    a.n_blocks = p->block_first[p->tp];
+    a.n_blocks = p->block_first[p->n_buckets];
     a.block_desc = a.tile_desc + a.n_tiles;
-    a.tp = p->tp;
+    a.tp = p->n_buckets;
     a.n_tensors = p->n_tensors;
     rose::RefreshArgs r{p->d_repl_list, p->d_repl_numel, p->n_repl};
-    return rose::launch_encode(a, new_dtype == ROSE_FP32_RNE, refresh ? &r : nullptr, arith ? 1 : 0, stream) == 0
+    const bool f32 = new_dtype == ROSE_FP32_RNE;
+    const int resident = p->resident[(f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0)];
+    return rose::launch_encode(a, f32, refresh ? &r : nullptr, arith ? 1 : 0, resident,
+                               p->worker_cap.load(std::memory_order_relaxed), stream) == 0
                ? ROSE_OK
                : ROSE_ERR_HIP;
 }
@@ -156,16 +174,15 @@ extern "C" rose_status rose_delta_encode_ex(const rose_plan *p, void *const *old
 
 static rose_status apply_common(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,
                                 void *const *dst_ptrs, void *stream) {
-    if (!p || !bucket || !dst_ptrs || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
+    if (!p || !bucket || !dst_ptrs || d < 0 || d >= p->n_buckets) return ROSE_ERR_ARG;
     if (payload != ROSE_PAYLOAD_NEW && payload != ROSE_PAYLOAD_ARITH) return ROSE_ERR_ARG;
     rose_status s = check_bucket(*bucket);
     if (s != ROSE_OK) return s;
     if (!aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
     rose::BucketDev b{bucket->idx, bucket->val, bucket->capacity, bucket->seg_off};
-    const rose::Piece *pieces = nullptr;
-    const int32_t *tile_piece = nullptr, *local_numel = nullptr;
-    s = device_tables(p, &pieces, &tile_piece, &local_numel);
+    s = device_tables(p);
     if (s != ROSE_OK) return s;
+    const int32_t *local_numel = p->d_local_numel + (size_t)(d / p->tp) * p->n_tensors;
     return rose::launch_apply(b, p->n_tensors, local_numel, dst_ptrs, payload, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
 }
 
@@ -181,13 +198,15 @@ extern "C" rose_status rose_delta_apply_ex(const rose_plan *p, int32_t d, const 
 
 extern "C" rose_status rose_dense_copy(const rose_plan *p, int32_t d, const void *const *new_ptrs,
                                        int32_t new_dtype, void *const *dst_ptrs, void *stream) {
-    if (!p || !new_ptrs || !dst_ptrs || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
+    if (!p || !new_ptrs || !dst_ptrs || d < 0 || d >= p->n_buckets) return ROSE_ERR_ARG;
     if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
     if (!aligned(new_ptrs, 8) || !aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
     rose::CopyArgs a;
     std::memset(&a, 0, sizeof a);
-    rose_status s = device_tables(p, &a.pieces, &a.tile_piece);
+    rose_status s = device_tables(p);
     if (s != ROSE_OK) return s;
+    a.pieces = p->d_pieces;
+    a.tile_piece = p->d_tile_piece;
     a.new_ptrs = new_ptrs;
     a.dst_ptrs = dst_ptrs;
     a.tile_begin = p->chain_first[d];
@@ -236,7 +255,7 @@ extern "C" rose_status rose_object_bytes(const rose_plan *p, int64_t n_entries, 
 static rose_status pack_common(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,
                                int64_t first_entry, int64_t n_entries, void *object, size_t object_bytes,
                                void *stream) {
-    if (!p || !bucket || !object || d < 0 || d >= p->tp || first_entry < 0 || n_entries < 0) return ROSE_ERR_ARG;
+    if (!p || !bucket || !object || d < 0 || d >= p->n_buckets || first_entry < 0 || n_entries < 0) return ROSE_ERR_ARG;
     if (payload != ROSE_PAYLOAD_NEW && payload != ROSE_PAYLOAD_ARITH) return ROSE_ERR_ARG;
     rose_status s = check_bucket(*bucket);
     if (s != ROSE_OK) return s;
@@ -264,11 +283,12 @@ extern "C" rose_status rose_object_apply(const rose_plan *p, const void *object,
     if (!p || !object || !dst_ptrs) return ROSE_ERR_ARG;
     if (!aligned(object, 16) || !aligned(dst_ptrs, 8)) return ROSE_ERR_ALIGN;
     if (object_bytes < rose::object_bytes_for(p->n_tensors, 0)) return ROSE_ERR_ARG;
-    const rose::Piece *pieces = nullptr;
-    const int32_t *tile_piece = nullptr, *local_numel = nullptr;
-    rose_status s = device_tables(p, &pieces, &tile_piece, &local_numel);
+    rose_status s = device_tables(p);
     if (s != ROSE_OK) return s;
-    return rose::launch_apply_object(object, object_bytes, p->n_tensors, local_numel, dst_ptrs, stream) == 0
+    // the validation pass leaves its verdict in one of the plan's words; tickets tell the calls apart
+    const uint64_t ticket = p->verdict_ticket.fetch_add(1, std::memory_order_relaxed) + 1;
+    return rose::launch_apply_object(object, object_bytes, p->n_tensors, p->n_buckets, p->tp, p->d_local_numel, dst_ptrs,
+                                     p->d_verdict + ticket % kVerdictSlots, ticket, stream) == 0
                ? ROSE_OK
                : ROSE_ERR_HIP;
 }
@@ -283,7 +303,7 @@ extern "C" rose_status rose_object_check(const rose_plan *p, const void *object,
     if (hipStreamSynchronize(st) != hipSuccess) return ROSE_ERR_HIP;
     int64_t n = 0;
     if (!rose::object_header_valid(h, p->n_tensors, object_bytes, &n)) return ROSE_ERR_ARG;
-    if ((int32_t)h[2] < 0 || (int32_t)h[2] >= p->tp) return ROSE_ERR_ARG;
+    if ((int32_t)h[2] < 0 || (int32_t)h[2] >= p->n_buckets) return ROSE_ERR_ARG;
     if (shard) *shard = (int32_t)h[2];
     if (first_entry) *first_entry = (int64_t)((uint64_t)h[4] | ((uint64_t)h[5] << 32));
     if (n_entries) *n_entries = n;

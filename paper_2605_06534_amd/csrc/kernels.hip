@@ -7,8 +7,6 @@
 // kernel reads each weight once with 128-bit loads and writes only the changed entries.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
-
 #include "rose_internal.h"
 
 namespace rose {
@@ -1620,20 +1618,67 @@ __host__ __device__ inline bool object_header_ok(const uint32_t *h, int32_t n_te
     return object_size(n_tensors, n) <= object_bytes;
 }
 
-__global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char *obj, size_t object_bytes, int32_t n_tensors,
-                                                                     const int32_t *local_numel, void *const *dst_ptrs) {
-    uint32_t h[9];
-    for (int i = 0; i < 9; ++i) h[i] = reinterpret_cast<const uint32_t *>(obj)[i];
-    int64_t n;
-    if (!object_header_ok(h, n_tensors, object_bytes, &n)) return;     // uniform: every thread leaves
+// the arrays inside an object whose header has passed object_header_ok
+__device__ __forceinline__ BucketDev object_arrays(const char *obj, int32_t n_tensors, int64_t n) {
     const size_t a_off = object_idx_off(n_tensors), b_off = a_off + up16(4 * (size_t)n);
     BucketDev b;
     b.idx = reinterpret_cast<int32_t *>(const_cast<char *>(obj + a_off));
     b.val = reinterpret_cast<uint16_t *>(const_cast<char *>(obj + b_off));
     b.capacity = n;
     b.seg_off = reinterpret_cast<int64_t *>(const_cast<char *>(obj + 64));
+    return b;
+}
+
+// Object apply runs as three launches on the stream: the verdict word is cleared, a pass over the
+// segment table and all indices writes `ticket` into it if the object is not in order, and the apply
+// pass leaves at once if it finds the ticket there.
+__global__ void object_clear_kernel(u64 *verdict) { *verdict = 0; }
+
+// Segment table: starts at 0, never decreases, ends at n.  Indices (escape bit masked off for
+// arithmetic payloads): strictly ascending inside a segment, which is what lets the apply pass
+// give every 64-byte piece of a tensor to exactly one wave.  An index may only fail to exceed its
+// predecessor where a segment starts.
+__global__ __launch_bounds__(256) void object_validate_kernel(const char *obj, size_t object_bytes, int32_t n_tensors,
+                                                              int32_t n_buckets, u64 *verdict, u64 ticket) {
+    uint32_t h[9];
+    for (int i = 0; i < 9; ++i) h[i] = reinterpret_cast<const uint32_t *>(obj)[i];
+    int64_t n;
+    if (!object_header_ok(h, n_tensors, object_bytes, &n) || h[2] >= (uint32_t)n_buckets) return;   // apply rejects it too
+    const BucketDev b = object_arrays(obj, n_tensors, n);
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t t = gid; t < n_tensors; t += stride) {
+        const int64_t lo = b.seg_off[t], hi = b.seg_off[t + 1];
+        bad |= lo < 0 || hi < lo || hi > n;
+    }
+    const int32_t m = h[8] ? 0x7FFFFFFF : -1;
+    for (int64_t e = gid + 1; e < n; e += stride) {
+        if ((b.idx[e] & m) <= (b.idx[e - 1] & m)) {
+            // allowed only if some segment starts at e: smallest t with seg_off[t] >= e
+            int32_t lo = 0, hi = n_tensors;
+            while (lo < hi) {
+                const int32_t mid = (lo + hi) >> 1;
+                if (b.seg_off[mid] < e) lo = mid + 1; else hi = mid;
+            }
+            bad |= b.seg_off[lo] != e;
+        }
+    }
+    if (bad) *verdict = ticket;
+}
+
+__global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char *obj, size_t object_bytes, int32_t n_tensors,
+                                                                     int32_t n_buckets, int32_t tp,
+                                                                     const int32_t *local_numel, void *const *dst_ptrs,
+                                                                     const u64 *verdict, u64 ticket) {
+    uint32_t h[9];
+    for (int i = 0; i < 9; ++i) h[i] = reinterpret_cast<const uint32_t *>(obj)[i];
+    int64_t n;
+    if (!object_header_ok(h, n_tensors, object_bytes, &n)) return;     // uniform: every thread leaves
+    if (h[2] >= (uint32_t)n_buckets) return;
+    if (*verdict == ticket) return;                                    // the validation pass found it out of order
+    const BucketDev b = object_arrays(obj, n_tensors, n);
     if (b.seg_off[0] != 0 || b.seg_off[n_tensors] != n) return;
-    apply_body(b, n_tensors, local_numel, dst_ptrs, (int)h[8]);
+    apply_body(b, n_tensors, local_numel + (size_t)(h[2] / (uint32_t)tp) * n_tensors, dst_ptrs, (int)h[8]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1750,22 +1795,20 @@ static EncodeKernel encode_variant(int new_is_f32, int refresh, int arith) {
     return table[(new_is_f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0)];
 }
 
-// Number of workgroups that fit on the device at once for the encode kernel.
-static int encode_resident(int new_is_f32, int refresh, int arith, int *resident) {
-    static int cached[8] = {0, 0, 0, 0, 0, 0, 0, 0};      // per kernel variant; the device set is homogeneous
-    const int v = (new_is_f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0);
-    if (!cached[v]) {
-        int dev = 0, cus = 0, per_cu = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_variant(new_is_f32, refresh, arith), kThreads, 0);
+// Number of workgroups of each encode kernel variant that fit on the current device at once.
+int encode_resident_all(int resident[8]) {
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return (int)e;
+    for (int v = 0; v < 8; ++v) {
+        int per_cu = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, encode_variant(v & 1, v & 2, v & 4), kThreads, 0);
         if (e != hipSuccess) return (int)e;
         if (per_cu < 1 || cus < 1) return (int)hipErrorInvalidValue;
         if (per_cu > ROSE_WGS_PER_CU) per_cu = ROSE_WGS_PER_CU;
-        cached[v] = cus * per_cu;
+        resident[v] = cus * per_cu;
     }
-    *resident = cached[v];
     return 0;
 }
 
@@ -1773,12 +1816,11 @@ static int encode_resident(int new_is_f32, int refresh, int arith, int *resident
 #define ROSE_SERVER_WGS 16          // workgroups of the grid that serve prefixes (kWaves servers each)
 #endif
 
-int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, int arith, void *stream) {
+int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, int arith, int resident,
+                  int worker_cap, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     EncodeArgs a = args;
-    int resident = 0;
-    int rc = encode_resident(new_is_f32, refresh ? 1 : 0, arith, &resident);
-    if (rc) return rc;
+    if (resident < 1) return (int)hipErrorInvalidValue;
     // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
     // a quarter of what is resident.  They are the first workgroups of the grid, so they are
     // resident before any worker waits for them.
@@ -1788,12 +1830,9 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *ref
     if (server_wgs < 1) server_wgs = 1;
     int workers = resident - server_wgs;
     if (workers > a.n_tiles) workers = a.n_tiles;
-    // tuning and test knob: fewer workers than the device holds (never fewer than the progress
+    // the caller's cap: fewer workers than the device holds (never fewer than the progress
     // argument below needs)
-    if (const char *e = std::getenv("ROSE_ENCODE_WORKERS")) {
-        const int w = std::atoi(e);
-        if (w > kBlock && w < workers) workers = w;
-    }
+    if (worker_cap > kBlock && worker_cap < workers) workers = worker_cap;
     // Progress with dynamic tickets: see the comment at struct Walk.  A worker that waits holds no
     // unpublished tile in the block it waits for or in an earlier one; what it waits for can still
     // need tickets of a partly handed-out group to be taken, by a worker that holds none of that
@@ -1838,13 +1877,18 @@ int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t fi
     return (int)hipGetLastError();
 }
 
-int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, const int32_t *local_numel,
-                        void *const *dst_ptrs, void *stream) {
+int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, int32_t n_buckets, int32_t tp,
+                        const int32_t *local_numel, void *const *dst_ptrs, unsigned long long *verdict,
+                        unsigned long long ticket, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = ((int64_t)(object_bytes / 6) + kApplyThreads - 1) / kApplyThreads;
     int blocks = chunks < 1 ? 1 : (chunks > ROSE_APPLY_BLOCKS ? ROSE_APPLY_BLOCKS : (int)chunks);
+    const int vblocks = blocks > 4096 ? 4096 : blocks;
+    hipLaunchKernelGGL(object_clear_kernel, dim3(1), dim3(1), 0, st, verdict);
+    hipLaunchKernelGGL(object_validate_kernel, dim3(vblocks), dim3(256), 0, st, static_cast<const char *>(object),
+                       object_bytes, n_tensors, n_buckets, verdict, ticket);
     hipLaunchKernelGGL(apply_object_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, static_cast<const char *>(object),
-                       object_bytes, n_tensors, local_numel, dst_ptrs);
+                       object_bytes, n_tensors, n_buckets, tp, local_numel, dst_ptrs, verdict, ticket);
     return (int)hipGetLastError();
 }
 

@@ -83,9 +83,21 @@ static bool sends(const rose_tensor_desc &t, int32_t ti, int32_t tp_src, int32_t
     return t.rule != ROSE_REPLICATED || ti % tp_src == src_rank;
 }
 
-// pieces of segment (t, d) that sender s of S holds, in ascending local index
+// Pipeline stage that holds a tensor (Sec. 4.2: the engine maps between TP and PP layouts of both
+// sides): the decoder layers are dealt to the pp stages in equal consecutive groups, tensors marked
+// ROSE_LAYER_FIRST (the embedding) go with the first stage, ROSE_LAYER_LAST (final norm, head) with
+// the last.  With one stage everything is held by it, whatever the layer field says.
+static int32_t stage_of(int32_t layer, int32_t n_layers, int32_t pp) {
+    if (pp <= 1 || layer == ROSE_LAYER_FIRST) return 0;
+    if (layer == ROSE_LAYER_LAST) return pp - 1;
+    return layer / (n_layers / pp);
+}
+
+// pieces of segment (t, d) that sender s of S holds, in ascending local index, for prefix chain
+// `chain` (= bucket); `here` = false: the sender does not hold the tensor, or the bucket's stage
+// does not receive it (an empty segment)
 static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int32_t D, int32_t S, int32_t s,
-                           std::vector<Piece> &out) {
+                           int32_t chain, bool here, std::vector<Piece> &out) {
     size_t first = out.size();
     // a part of `len` elements in runs of `run`: the sender's slice advances by src_stride per run,
     // the destination's local index by lstride per run (both equal to run when contiguous)
@@ -96,7 +108,7 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
         std::memset(&p, 0, sizeof p);
         p.src_off = src_off;
         p.tensor = ti;
-        p.shard = d;
+        p.shard = chain;
         p.local_base = (int32_t)local_base;
         p.len = (int32_t)len;
         const bool src_strided = run < len && src_stride != run;
@@ -123,7 +135,7 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
     };
     const int64_t R = t.rows, C = t.cols;
     int64_t lo, hi;
-    if (sends(t, ti, S, s)) {
+    if (here && sends(t, ti, S, s)) {
         switch (t.rule) {
         case ROSE_REPLICATED:
             add(0, R * C, 0, R * C, R * C, R * C);
@@ -177,23 +189,32 @@ static void segment_pieces(const rose_tensor_desc &t, int32_t ti, int32_t d, int
         Piece p;
         std::memset(&p, 0, sizeof p);
         p.tensor = ti;
-        p.shard = d;
+        p.shard = chain;
         p.run = 0;
         out.push_back(p);
     }
     out[first].flags |= rose::kPieceFirst;
 }
 
-extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
-                                                  int32_t tp_src, int32_t src_rank, rose_plan **out) {
+extern "C" rose_status rose_shard_plan_create_pp(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
+                                                 int32_t tp_src, int32_t src_rank, int32_t n_layers, int32_t pp_src,
+                                                 int32_t stage_src, int32_t pp_dst, rose_plan **out) {
     if (!out) return ROSE_ERR_ARG;
     *out = nullptr;
     if (!tensors || n_tensors < 1 || tp < 1 || tp_src < 1 || src_rank < 0 || src_rank >= tp_src) return ROSE_ERR_ARG;
-    if (tp > ROSE_MAX_TP || tp_src > ROSE_MAX_TP) return ROSE_ERR_UNSUPPORTED;
+    if (pp_src < 1 || pp_dst < 1 || stage_src < 0 || stage_src >= pp_src || n_layers < 0) return ROSE_ERR_ARG;
+    if (tp > ROSE_MAX_TP || tp_src > ROSE_MAX_TP || pp_dst > ROSE_MAX_TP || tp * pp_dst > ROSE_MAX_TP ||
+        pp_src > (1 << 20))
+        return ROSE_ERR_UNSUPPORTED;
+    const bool staged = pp_src > 1 || pp_dst > 1;
+    if (staged && (n_layers < 1 || n_layers % pp_src || n_layers % pp_dst)) return ROSE_ERR_SHAPE;
     for (int32_t i = 0; i < n_tensors; ++i) {
         rose_status s = check_desc(tensors[i], tp, true);
         if (s == ROSE_OK) s = check_desc(tensors[i], tp_src, false);
         if (s == ROSE_OK && tensors[i].src_groups > 0 && tensors[i].src_groups % tp_src) s = ROSE_ERR_SHAPE;
+        if (s == ROSE_OK && staged && tensors[i].layer != ROSE_LAYER_FIRST && tensors[i].layer != ROSE_LAYER_LAST &&
+            (tensors[i].layer < 0 || tensors[i].layer >= n_layers))
+            s = ROSE_ERR_ARG;
         if (s != ROSE_OK) return s;
     }
     rose_plan *p = new (std::nothrow) rose_plan;
@@ -202,18 +223,30 @@ extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensor
         p->tp = tp;
         p->tp_src = tp_src;
         p->src_rank = src_rank;
+        p->n_layers = n_layers;
+        p->pp_src = pp_src;
+        p->stage_src = stage_src;
+        p->pp_dst = pp_dst;
+        p->n_buckets = tp * pp_dst;
         p->n_tensors = n_tensors;
         p->tensors.assign(tensors, tensors + n_tensors);
+        p->stage_src_of.resize(n_tensors);
+        p->stage_dst_of.resize(n_tensors);
         p->global_base.resize(n_tensors + 1);
         p->global_base[0] = 0;
-        for (int32_t i = 0; i < n_tensors; ++i)
+        for (int32_t i = 0; i < n_tensors; ++i) {
             p->global_base[i + 1] = p->global_base[i] + tensors[i].rows * tensors[i].cols;
+            p->stage_src_of[i] = stage_of(tensors[i].layer, n_layers, pp_src);
+            p->stage_dst_of[i] = stage_of(tensors[i].layer, n_layers, pp_dst);
+        }
         int64_t n_tiles = 0;
-        for (int32_t d = 0; d < tp; ++d) {
-            p->chain_first[d] = (int32_t)n_tiles;
+        for (int32_t b = 0; b < p->n_buckets; ++b) {
+            const int32_t stage_dst = b / tp, d = b % tp;
+            p->chain_first[b] = (int32_t)n_tiles;
             for (int32_t i = 0; i < n_tensors; ++i) {
                 size_t first = p->pieces.size();
-                segment_pieces(tensors[i], i, d, tp, tp_src, src_rank, p->pieces);
+                const bool here = p->stage_src_of[i] == stage_src && p->stage_dst_of[i] == stage_dst;
+                segment_pieces(tensors[i], i, d, tp, tp_src, src_rank, b, here, p->pieces);
                 for (size_t k = first; k < p->pieces.size(); ++k) {
                     Piece &pc = p->pieces[k];
                     int64_t nt = pc.len == 0 ? 1 : ((int64_t)pc.len + rose::kTile - 1) / rose::kTile;
@@ -227,11 +260,11 @@ extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensor
                 }
             }
         }
-        for (int32_t d = tp; d <= ROSE_MAX_TP; ++d) p->chain_first[d] = (int32_t)n_tiles;
+        for (int32_t b = p->n_buckets; b <= ROSE_MAX_TP; ++b) p->chain_first[b] = (int32_t)n_tiles;
         int32_t n_blocks = 0;
-        for (int32_t d = 0; d <= ROSE_MAX_TP; ++d) {
-            p->block_first[d] = n_blocks;
-            if (d < tp) n_blocks += (p->chain_first[d + 1] - p->chain_first[d] + rose::kBlock - 1) / rose::kBlock;
+        for (int32_t b = 0; b <= ROSE_MAX_TP; ++b) {
+            p->block_first[b] = n_blocks;
+            if (b < p->n_buckets) n_blocks += (p->chain_first[b + 1] - p->chain_first[b] + rose::kBlock - 1) / rose::kBlock;
         }
     } catch (...) {
         delete p;
@@ -241,13 +274,47 @@ extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensor
     return ROSE_OK;
 }
 
+extern "C" rose_status rose_shard_plan_create_src(const rose_tensor_desc *tensors, int32_t n_tensors, int32_t tp,
+                                                  int32_t tp_src, int32_t src_rank, rose_plan **out) {
+    return rose_shard_plan_create_pp(tensors, n_tensors, tp, tp_src, src_rank, 0, 1, 0, 1, out);
+}
+
 extern "C" rose_status rose_shard_plan_create(const rose_tensor_desc *tensors, int32_t n_tensors,
                                               int32_t tp, rose_plan **out) {
-    return rose_shard_plan_create_src(tensors, n_tensors, tp, 1, 0, out);
+    return rose_shard_plan_create_pp(tensors, n_tensors, tp, 1, 0, 0, 1, 0, 1, out);
 }
 
 extern "C" int32_t rose_plan_n_tensors(const rose_plan *p) { return p ? p->n_tensors : -1; }
 extern "C" int32_t rose_plan_tp(const rose_plan *p) { return p ? p->tp : -1; }
+extern "C" int32_t rose_plan_n_buckets(const rose_plan *p) { return p ? p->n_buckets : -1; }
+
+extern "C" rose_status rose_plan_stage_of(const rose_plan *p, int32_t t, int32_t *stage_src, int32_t *stage_dst) {
+    if (!p || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
+    if (stage_src) *stage_src = p->stage_src_of[t];
+    if (stage_dst) *stage_dst = p->stage_dst_of[t];
+    return ROSE_OK;
+}
+
+// does an encode launch with these flags dereference the old / new pointers of tensor t?
+static bool tensor_is_read(const rose_plan *p, int32_t t, uint32_t flags) {
+    const rose_tensor_desc &d = p->tensors[t];
+    if (p->stage_src_of[t] != p->stage_src || d.rows * d.cols == 0) return false;
+    if (sends(d, t, p->tp_src, p->src_rank)) return true;
+    return (flags & ROSE_ENCODE_REFRESH) != 0;     // held but not sent (replicated): only the refresh copy touches it
+}
+
+extern "C" rose_status rose_plan_tensor_is_read(const rose_plan *p, int32_t t, uint32_t flags, int32_t *is_read) {
+    if (!p || !is_read || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
+    if (flags & ~(uint32_t)(ROSE_ENCODE_REFRESH | ROSE_ENCODE_ARITH)) return ROSE_ERR_ARG;
+    *is_read = tensor_is_read(p, t, flags) ? 1 : 0;
+    return ROSE_OK;
+}
+
+extern "C" rose_status rose_plan_set_worker_cap(rose_plan *p, int32_t workers) {
+    if (!p || workers < 0) return ROSE_ERR_ARG;
+    p->worker_cap.store(workers, std::memory_order_relaxed);
+    return ROSE_OK;
+}
 
 extern "C" rose_status rose_plan_tensor_base(const rose_plan *p, int32_t t, int64_t *global_base) {
     if (!p || !global_base || t < 0 || t > p->n_tensors) return ROSE_ERR_ARG;
@@ -256,13 +323,13 @@ extern "C" rose_status rose_plan_tensor_base(const rose_plan *p, int32_t t, int6
 }
 
 extern "C" rose_status rose_plan_local_numel(const rose_plan *p, int32_t t, int32_t d, int64_t *numel) {
-    if (!p || !numel || t < 0 || t >= p->n_tensors || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
-    *numel = local_numel(p->tensors[t], p->tp);
+    if (!p || !numel || t < 0 || t >= p->n_tensors || d < 0 || d >= p->n_buckets) return ROSE_ERR_ARG;
+    *numel = p->stage_dst_of[t] == d / p->tp ? local_numel(p->tensors[t], p->tp) : 0;
     return ROSE_OK;
 }
 
 extern "C" rose_status rose_plan_bucket_capacity(const rose_plan *p, int32_t d, int64_t *max_entries) {
-    if (!p || !max_entries || d < 0 || d >= p->tp) return ROSE_ERR_ARG;
+    if (!p || !max_entries || d < 0 || d >= p->n_buckets) return ROSE_ERR_ARG;
     int64_t s = 0;                              // everything this sender can send to shard d
     for (const Piece &pc : p->pieces)
         if (pc.shard == d) s += pc.len;
@@ -272,7 +339,7 @@ extern "C" rose_status rose_plan_bucket_capacity(const rose_plan *p, int32_t d, 
 
 extern "C" rose_status rose_plan_src_numel(const rose_plan *p, int32_t t, int64_t *numel) {
     if (!p || !numel || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
-    *numel = local_numel(p->tensors[t], p->tp_src);
+    *numel = p->stage_src_of[t] == p->stage_src ? local_numel(p->tensors[t], p->tp_src) : 0;
     return ROSE_OK;
 }
 
@@ -286,7 +353,7 @@ extern "C" rose_status rose_plan_workspace_bytes(const rose_plan *p, size_t *byt
     if (!p || !bytes) return ROSE_ERR_ARG;
     // header + one 64-bit descriptor per tile + one per block of tiles
     *bytes = rose::kWsHeaderBytes +
-             (p->tile_piece.size() + (size_t)p->block_first[p->tp]) * sizeof(unsigned long long);
+             (p->tile_piece.size() + (size_t)p->block_first[p->n_buckets]) * sizeof(unsigned long long);
     return ROSE_OK;
 }
 
@@ -295,6 +362,7 @@ extern "C" rose_status rose_plan_workspace_bytes(const rose_plan *p, size_t *byt
 extern "C" rose_status rose_plan_map_index(const rose_plan *p, int32_t t, int64_t g, int32_t *d_first,
                                            int32_t *n_dest, int32_t *local) {
     if (!p || !d_first || !n_dest || !local || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
+    if (p->stage_src_of[t] != p->stage_src) return ROSE_ERR_ARG;          // not held by this sender
     if (g < 0 || g >= local_numel(p->tensors[t], p->tp_src)) return ROSE_ERR_ARG;
     int found = 0;
     for (const Piece &pc : p->pieces) {

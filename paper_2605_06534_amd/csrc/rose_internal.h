@@ -1,6 +1,7 @@
 // Internal declarations shared by the host planner, the C ABI and the kernel launchers.
 #pragma once
 
+#include <atomic>
 #include <cstddef>
 #include <cstdint>
 #include <mutex>
@@ -125,14 +126,24 @@ struct RefreshArgs {
     const int64_t *numel;
     int32_t n;
 };
-int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, int arith, void *stream);
+// resident: workgroups of this kernel variant that fit on the device at once (encode_resident_all);
+// worker_cap: 0, or the most workgroups that may walk tiles
+int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, int arith, int resident,
+                  int worker_cap, void *stream);
+// resident workgroups of each of the eight encode kernel variants on the current device
+// (index: fp32 input + 2 * refresh + 4 * arithmetic payload)
+int encode_resident_all(int resident[8]);
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
                  int arith, void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
 int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, int32_t payload,
                 void *object, void *stream);
-int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, const int32_t *local_numel,
-                        void *const *dst_ptrs, void *stream);
+// local_numel: [n_stages][n_tensors]; the object's shard word b selects row b / tp.  verdict: one word of
+// device memory that belongs to this call until its kernels have run; ticket: a value no other call
+// that shares the word uses.
+int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tensors, int32_t n_buckets, int32_t tp,
+                        const int32_t *local_numel, void *const *dst_ptrs, unsigned long long *verdict,
+                        unsigned long long ticket, void *stream);
 size_t object_bytes_for(int32_t n_tensors, int64_t n);
 bool object_header_valid(const uint32_t *header, int32_t n_tensors, size_t object_bytes, int64_t *n);
 int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
@@ -141,23 +152,37 @@ int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chun
 
 }  // namespace rose
 
+// words of device memory that object applies use to hand the validation pass's verdict to the apply pass
+constexpr int kVerdictSlots = 4096;
+
 struct rose_plan {
     int32_t tp_src = 1, src_rank = 0;          // the sender holds shard src_rank of tp_src of every tensor
     int32_t tp = 0;
+    // pipeline stages (Sec. 4.2: TP and PP on both sides): the sender is stage stage_src of pp_src and holds
+    // the tensors of that stage only; the receiving side has pp_dst stages of tp shards each.  Bucket (and
+    // prefix chain) b = stage * tp + shard.
+    int32_t n_layers = 0, pp_src = 1, stage_src = 0, pp_dst = 1;
+    int32_t n_buckets = 0;                     // tp * pp_dst
     int32_t n_tensors = 0;
     std::vector<rose_tensor_desc> tensors;
+    std::vector<int32_t> stage_src_of, stage_dst_of;   // [n_tensors] stage that holds each tensor on either side
     std::vector<int64_t> global_base;          // [n_tensors + 1]
     std::vector<rose::Piece> pieces;
     std::vector<int32_t> tile_piece;           // piece of each tile
     int32_t chain_first[ROSE_MAX_TP + 1] = {0};
     int32_t block_first[ROSE_MAX_TP + 1] = {0};
-    // device copies of pieces / tile_piece, made on first use on a device
+    mutable std::atomic<int32_t> worker_cap{0};     // rose_plan_set_worker_cap
+    mutable std::atomic<uint64_t> verdict_ticket{0};
+    // device copies of pieces / tile_piece, made on first use on a device (the only device the plan is used on)
     mutable std::mutex mu;
     mutable int device = -1;
     mutable rose::Piece *d_pieces = nullptr;
     mutable int32_t *d_tile_piece = nullptr;
-    mutable int32_t *d_local_numel = nullptr;  // [n_tensors] elements of a shard's copy of each tensor
-    mutable int32_t *d_repl_list = nullptr;    // replicated tensors (ordinals) and their sizes
+    mutable int32_t *d_local_numel = nullptr;  // [pp_dst][n_tensors] elements of a shard's copy of each tensor
+                                               // (0 where the stage does not hold the tensor)
+    mutable int32_t *d_repl_list = nullptr;    // replicated tensors this sender holds (ordinals) and their sizes
     mutable int64_t *d_repl_numel = nullptr;
     mutable int32_t n_repl = 0;
+    mutable unsigned long long *d_verdict = nullptr;   // [kVerdictSlots]
+    mutable int resident[8] = {0};             // see encode_resident_all
 };

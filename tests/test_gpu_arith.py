@@ -224,7 +224,7 @@ def test_arith_every_pattern_pair():
         del old, dst, pos, w_esc, w_val
 
 
-def test_arith_few_workers_dense_changes(monkeypatch):
+def test_arith_few_workers_dense_changes():
     """Arithmetic payloads through the regime where tiles are counted first and walked again (two
     tickets of one group in a row) and where tiles are too dense to park, with and without refresh."""
     ts = models.decoder(2, 1024, 16, 16, 64, 2816, 4096, fused=True)
@@ -232,8 +232,8 @@ def test_arith_few_workers_dense_changes(monkeypatch):
     for workers, p, flags in [(66, 0.6, R.ENCODE_ARITH), (70, 0.9, R.ENCODE_ARITH | R.ENCODE_REFRESH),
                               (97, 1.0, R.ENCODE_ARITH)]:
         print("case: arith few workers=%d p=%g flags=%d" % (workers, p, flags), flush=True)
-        monkeypatch.setenv("ROSE_ENCODE_WORKERS", str(workers))
         c = any_case(ts, 2, p, seed=workers)
+        c.plan.set_worker_cap(workers)
         check_arith(c, flags=flags)
         pairs += int(c.ws.view(torch.int32)[2])
     assert pairs > 0, "the pair handling never ran: the test does not reach what it is for"

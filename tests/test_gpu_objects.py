@@ -109,6 +109,56 @@ def test_malformed_objects_change_nothing_and_errors_are_reported():
         R.bucket_pack(c.plan, 0, c.buckets[0], -1, n, good)
 
 
+def test_object_with_indices_out_of_order_changes_nothing():
+    """The apply kernel gives every 64-byte piece of a tensor to one wave on the strength of the
+    entries' order; an object whose indices do not ascend inside a segment is turned away whole,
+    like one with a bad header."""
+    print("case: transport objects with shuffled indices", flush=True)
+    ts, c, want = encode_case(1, 0.05, seed=33)
+    recs = c.records()
+    total = R.bucket_check(c.plan, c.buckets[0])
+    n = min(total, 70000)
+    good = torch.zeros(R.object_bytes(c.plan, n), dtype=torch.uint8, device="cuda")
+    R.bucket_pack(c.plan, 0, c.buckets[0], 0, n, good)
+    torch.cuda.synchronize()
+    old_bits = [r["old"] for r in recs]
+    ref = c.shard_init(0, old_bits)
+    idx_off = oracle.object_bytes(len(ts), 0)            # where the index array starts
+    seg = good[64:64 + 8 * (len(ts) + 1)].view(torch.int64).cpu().numpy()
+
+    def unchanged_after(obj):
+        dst = c.shard_init(0, old_bits)
+        R.object_apply(c.plan, obj, R.ptr_table(dst))
+        torch.cuda.synchronize()
+        return all(torch.equal(a, b) for a, b in zip(dst, ref))
+
+    assert not unchanged_after(good)
+    t_big = int(np.argmax(np.diff(seg)))                 # a segment with many entries
+    a, b = int(seg[t_big]), int(seg[t_big + 1])
+    assert b - a > 300
+    for kind in ("swap_neighbours", "swap_far", "duplicate", "last_two", "segment_table_decreases"):
+        bad = good.clone()
+        idx = bad[idx_off:idx_off + 4 * n].view(torch.int32)
+        if kind == "swap_neighbours":
+            i = a + 100
+            idx[i], idx[i + 1] = int(idx[i + 1]), int(idx[i])
+        elif kind == "swap_far":                         # two chunks of 64 entries apart
+            i, j = a + 10, a + 200
+            idx[i], idx[j] = int(idx[j]), int(idx[i])
+        elif kind == "duplicate":
+            idx[a + 65] = int(idx[a + 64])
+        elif kind == "last_two":
+            idx[b - 1] = int(idx[b - 2])
+        else:
+            st = bad[64:64 + 8 * (len(ts) + 1)].view(torch.int64)
+            st[t_big + 1] = a - 1 if a > 0 else 0
+            if a == 0:
+                st[t_big + 1], st[t_big] = 0, 5
+        assert unchanged_after(bad), kind
+    # a drop at a segment start is what a well-formed object has: still applied
+    assert not unchanged_after(good)
+
+
 def test_objects_of_the_7b_workload_at_64_mb():
     """Full-size: shard 1's stream of the 7B workload at 5 % cut into 64 MB objects (the paper's
     push size), applied in reverse order; the result equals applying the bucket."""

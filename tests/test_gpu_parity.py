@@ -135,7 +135,7 @@ def test_fp32_rounding_special_values():
     assert np.array_equal(want[0]["val"], rb[rb != 0])
 
 
-def test_few_workers_dense_changes(monkeypatch):
+def test_few_workers_dense_changes():
     """Few workers and tiles that fill the LDS ring: workers wait often and take tickets at a low
     rate, so one worker gets two tickets of one group of blocks in a row; the kernel then
     publishes that pair's counts before it may wait again.  The result must not depend on any of
@@ -144,8 +144,8 @@ def test_few_workers_dense_changes(monkeypatch):
     pairs = 0
     for workers, p in [(65, 0.9), (66, 0.6), (70, 0.9), (97, 1.0), (130, 0.3)]:
         print("case: few workers=%d p=%g seed=%d" % (workers, p, workers), flush=True)
-        monkeypatch.setenv("ROSE_ENCODE_WORKERS", str(workers))
         c = bern_case(ts, 2, p, seed=workers)
+        c.plan.set_worker_cap(workers)
         full_parity(c, check_dense=False)
         n = int(c.ws.view(torch.int32)[2])
         print("  same-group ticket pairs handled: %d" % n, flush=True)

@@ -71,15 +71,15 @@ def test_refresh_fp32_master():
     check_refresh(Case(ts, 4, olds, news))
 
 
-def test_refresh_few_workers_dense(monkeypatch):
+def test_refresh_few_workers_dense():
     """The regime where tiles are walked twice (two tickets of one group in a row): a tile must
     not be refreshed before its second walk."""
     print("case: refresh few workers", flush=True)
     ts = models.decoder(2, 1024, 16, 16, 64, 2816, 4096, fused=True)
     pairs = 0
     for workers, p in [(66, 0.6), (70, 0.9)]:
-        monkeypatch.setenv("ROSE_ENCODE_WORKERS", str(workers))
         c = bern_case(ts, 2, p, seed=workers)
+        c.plan.set_worker_cap(workers)
         recs = c.records()
         want = oracle.encode_model(recs, 2)
         R.delta_encode_refresh(c.plan, c.old_tab, c.new_tab, c.new_dtype, c.buckets, c.ws)

@@ -224,3 +224,86 @@ def test_planner_matches_oracle_map_on_random_parameter_sets():
                 assert plan.map_index(i, int(g)) == want, (seed, i, int(g))
         for d in range(tp):
             assert plan.bucket_capacity(d) == cap[d]
+
+
+def test_which_pointer_table_entries_a_launch_reads():
+    """A replicated tensor is sent by one sender (ordinal mod tp_src); the others read its pointers
+    only when they refresh their own copy.  Empty tensors are never read."""
+    ts = [dict(name="n0", rows=1, cols=64, rule=R.REPLICATED, sections=None),
+          dict(name="w", rows=16, cols=8, rule=R.SPLIT_ROWS, sections=None),
+          dict(name="n1", rows=1, cols=64, rule=R.REPLICATED, sections=None),
+          dict(name="empty", rows=0, cols=8, rule=R.SPLIT_ROWS, sections=None),
+          dict(name="n2", rows=1, cols=64, rule=R.REPLICATED, sections=None)]
+    for s in range(2):
+        plan = R.shard_plan(ts, 4, 2, s)
+        sent = [plan.tensor_is_read(t) for t in range(len(ts))]
+        assert sent == [s == 0, True, s == 0, False, s == 0]
+        assert [plan.tensor_is_read(t, R.ENCODE_REFRESH) for t in range(len(ts))] == [True, True, True, False, True]
+        assert [plan.tensor_is_read(t, R.ENCODE_ARITH) for t in range(len(ts))] == sent
+    with pytest.raises(R.RoseError):
+        R.shard_plan(ts, 4).tensor_is_read(0, 8)
+    with pytest.raises(R.RoseError):
+        R.shard_plan(ts, 4).tensor_is_read(5)
+
+
+@pytest.mark.parametrize("pp_src,pp_dst,tp_src,tp", [(2, 1, 2, 4), (1, 2, 1, 2), (4, 2, 2, 1), (2, 4, 1, 4), (2, 2, 4, 2)])
+def test_pipeline_plan_matches_oracle_stages_and_maps(pp_src, pp_dst, tp_src, tp):
+    """The plan of a sender (tensor-parallel rank s in pipeline stage st) lists the whole model: its
+    tables must hold, for every element of every tensor of the sender's stage, the oracle's
+    destination under the receiving side's degree, in the bucket of the oracle's receiving stage,
+    and nothing for the tensors of other stages."""
+    n_layers = 4
+    ts = models.decoder(n_layers, 32, 4, 4, 8, 48, 64, fused=True)
+    for st in range(pp_src):
+        for s in range(tp_src):
+            plan = R.shard_plan(ts, tp, tp_src, s, n_layers, pp_src, st, pp_dst)
+            assert plan.n_buckets == tp * pp_dst and plan.tp == tp
+            cap = [0] * plan.n_buckets
+            for i, t in enumerate(ts):
+                held = oracle.stage_of(t["layer"], n_layers, pp_src) == st
+                to = oracle.stage_of(t["layer"], n_layers, pp_dst)
+                assert plan.stage_of(i) == (oracle.stage_of(t["layer"], n_layers, pp_src), to)
+                assert plan.src_numel(i) == (oracle.local_numel(t["rule"], t["rows"], t["cols"], tp_src) if held else 0)
+                for b in range(plan.n_buckets):
+                    want = oracle.local_numel(t["rule"], t["rows"], t["cols"], tp) if b // tp == to else 0
+                    assert plan.local_numel(i, b) == want
+                assert plan.tensor_is_read(i) == (held and (t["rule"] != R.REPLICATED or i % tp_src == s))
+                if not held:
+                    with pytest.raises(R.RoseError):
+                        plan.map_index(i, 0)
+                    continue
+                sends = t["rule"] != R.REPLICATED or i % tp_src == s
+                for r in range(0, t["rows"], 3):
+                    for c in range(0, t["cols"], 5):
+                        s_first, n_src, g = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], tp_src, r, c)
+                        if not (s_first <= s < s_first + n_src):
+                            continue
+                        d_first, n_dest, local = oracle.shard_map(t["rule"], t["rows"], t["cols"], t["sections"], tp, r, c)
+                        got = plan.map_index(i, g)
+                        if sends:
+                            assert got == (to * tp + d_first, n_dest, local), (st, s, i, r, c)
+                        else:
+                            assert got[1] == 0
+                if sends:
+                    # everything of the tensor that this sender holds lands in the receiving stage's buckets
+                    n = oracle.local_numel(t["rule"], t["rows"], t["cols"], tp_src)
+                    per = n * (tp if t["rule"] == R.REPLICATED else 1)
+                    cap[to * tp] += per       # compared with the sum over the stage's buckets below
+            got_caps = [plan.bucket_capacity(b) for b in range(plan.n_buckets)]
+            for stage in range(pp_dst):
+                assert sum(got_caps[stage * tp:(stage + 1) * tp]) == cap[stage * tp]
+
+
+def test_pipeline_plan_argument_errors():
+    ts = models.decoder(4, 32, 4, 4, 8, 48, 64, fused=True)
+    for tp, kw, status in [(4, dict(n_layers=4, pp_src=3), binding.ERR_SHAPE),
+                           (4, dict(n_layers=4, pp_dst=3), binding.ERR_SHAPE),
+                           (4, dict(n_layers=4, pp_src=2, stage_src=2), binding.ERR_ARG),
+                           (4, dict(n_layers=2, pp_src=2), binding.ERR_ARG),        # layer 3 of a 2-layer model
+                           (4, dict(n_layers=0, pp_src=2), binding.ERR_SHAPE),
+                           (8, dict(n_layers=4, pp_dst=4), binding.ERR_UNSUPPORTED)]:   # 8 * 4 buckets
+        with pytest.raises(R.RoseError) as e:
+            R.shard_plan(ts, tp, **kw)
+        assert e.value.status == status, kw
+    # one stage on both sides ignores the layer field altogether
+    R.shard_plan([dict(t, layer=99) for t in ts], 4)
