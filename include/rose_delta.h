@@ -23,7 +23,8 @@
  *     return ROSE_ERR_ARG.  Make one plan per device.
  *   - Errors that the host can see are returned before anything is queued.
  *     No exception crosses this boundary.  The library keeps no state outside plan
- *     handles.
+ *     handles, except the built-in scratch array of rose_delta_encode_static (one
+ *     per device, see there).
  *   - Weights are 16-bit patterns (bf16).  "Changed" means the two patterns
  *     differ; an entry carries the new pattern and applying it overwrites.
  *   - Entry coordinates are int32 flat indices local to the destination shard's
@@ -49,7 +50,9 @@ typedef enum {
     ROSE_ERR_CAPACITY = 3,    /* a bucket was too small (see rose_bucket_check) */
     ROSE_ERR_ALIGN = 4,       /* a bucket or workspace pointer is not aligned as required */
     ROSE_ERR_HIP = 5,         /* a HIP runtime call failed (no GPU, launch failure), or an encode launch gave up */
-    ROSE_ERR_UNSUPPORTED = 6  /* a destination shard's local tensor has 2^31 or more elements, tp > ROSE_MAX_TP */
+    ROSE_ERR_UNSUPPORTED = 6, /* a destination shard's local tensor has 2^31 or more elements, tp > ROSE_MAX_TP */
+    ROSE_ERR_SCRATCH = 7      /* rose_delta_encode_static: the plan was not uploaded to this device, or it needs
+                                 more scratch than the built-in array holds */
 } rose_status;
 
 /* How the receiver's layout cuts a row-major (rows, cols) tensor into tp shards. */
@@ -162,9 +165,9 @@ rose_status rose_shard_plan_create_pp(const rose_tensor_desc *tensors, int32_t n
 void rose_shard_plan_destroy(rose_plan *plan);
 /*
  * Makes the plan resident on the current device (HOST call; allocates and copies the plan's tables,
- * asks the runtime how many workgroups of each kernel fit) and
+ * asks the runtime how many workgroups of each kernel fit, looks up the built-in scratch array) and
  * binds the plan to that device.  The other device calls do this by themselves on first use; call it
- * ahead of time where a later call must not allocate (graph capture).
+ * ahead of time where a later call must not allocate (graph capture, rose_delta_encode_static).
  * Idempotent.  ROSE_ERR_HIP if the runtime fails, ROSE_ERR_ARG if the plan is bound to another device.
  */
 rose_status rose_plan_upload(const rose_plan *plan);
@@ -288,6 +291,25 @@ rose_status rose_delta_encode_ex(const rose_plan *plan, void *const *old_ptrs, c
                                  void *workspace, size_t workspace_bytes, void *stream);
 rose_status rose_delta_apply_ex(const rose_plan *plan, int32_t d, const rose_bucket *bucket, int32_t payload,
                                 void *const *dst_ptrs, void *stream);
+
+/*
+ * rose_delta_encode_ex for callers that cannot allocate or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch that the kernels need
+ * (tile and block descriptors, ticket counter, abort flag) lives in an array built into the library,
+ * ROSE_STATIC_SCRATCH_BYTES per device, held from the library's load to the end of the process.
+ * The call allocates nothing and frees nothing; it queues the same kernels as rose_delta_encode_ex and
+ * the buckets come out identical.
+ *   - the plan must be resident on the current device already (rose_plan_upload, or any earlier
+ *     device call on it): otherwise ROSE_ERR_SCRATCH, nothing queued;
+ *   - rose_plan_workspace_bytes(plan) must not exceed ROSE_STATIC_SCRATCH_BYTES (about 6 million
+ *     tiles, i.e. 50 G elements): otherwise ROSE_ERR_SCRATCH, nothing queued;
+ *   - every call on a device shares that device's array, which keeps the previous call's contents
+ *     (the launch clears what it uses first): calls that overlap in time on one device race, whatever
+ *     their streams or plans.  Order them on one stream.
+ */
+#define ROSE_STATIC_SCRATCH_BYTES (48u << 20)
+rose_status rose_delta_encode_static(const rose_plan *plan, void *const *old_ptrs, const void *const *new_ptrs,
+                                     int32_t new_dtype, uint32_t flags, const rose_bucket *buckets, void *stream);
 
 /*
  * delta_apply (Sec. 4.2, sparsity-aware transfer: a receiver applies its own shard only; App. F S2D): writes every

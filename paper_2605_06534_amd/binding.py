@@ -14,8 +14,9 @@ ROSE_MAX_TP = 16
 ROSE_MAX_SECTIONS = 4
 REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
 BF16, FP32_RNE = 0, 1
-OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED = range(7)
+OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED, ERR_SCRATCH = range(8)
 LAYER_FIRST, LAYER_LAST = -1, -2
+STATIC_SCRATCH_BYTES = 48 << 20
 
 _LIB_PATH = os.environ.get("ROSE_DELTA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
                                                             "librose_delta.so")
@@ -59,6 +60,7 @@ _SIGS = {
     "rose_delta_encode": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
     "rose_delta_encode_refresh": (_i32, [_vp, _vp, _vp, _i32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
     "rose_delta_encode_ex": (_i32, [_vp, _vp, _vp, _i32, ctypes.c_uint32, _P(CBucket), _vp, ctypes.c_size_t, _vp]),
+    "rose_delta_encode_static": (_i32, [_vp, _vp, _vp, _i32, ctypes.c_uint32, _P(CBucket), _vp]),
     "rose_delta_apply": (_i32, [_vp, _i32, _P(CBucket), _vp, _vp]),
     "rose_delta_apply_ex": (_i32, [_vp, _i32, _P(CBucket), _i32, _vp, _vp]),
     "rose_dense_copy": (_i32, [_vp, _i32, _vp, _i32, _vp, _vp]),
@@ -257,6 +259,13 @@ def delta_encode_ex(plan, old_tab, new_tab, new_dtype, flags, buckets, ws, strea
     _check(_lib.rose_delta_encode_ex(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, flags, cb,
                                      ws.data_ptr(), ws.numel() * ws.element_size(), _stream(stream)),
            "delta_encode_ex")
+
+
+def delta_encode_static(plan, old_tab, new_tab, new_dtype, flags, buckets, stream=None):
+    """delta_encode_ex on the library's built-in scratch: no workspace, no allocation (plan.upload() first)."""
+    cb = (CBucket * plan.n_buckets)(*[b.c() for b in buckets])
+    _check(_lib.rose_delta_encode_static(plan._h, old_tab.data_ptr(), new_tab.data_ptr(), new_dtype, flags, cb,
+                                         _stream(stream)), "delta_encode_static")
 
 
 def delta_apply_ex(plan, d, bucket, payload, dst_tab, stream=None):

@@ -10,13 +10,15 @@ namespace {
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Copy the piece and tile tables to the current device once; later calls on the same device
-// reuse them.  A plan is bound to the first device it is used on.
-rose_status device_tables(const rose_plan *p) {
+// reuse them.  A plan is bound to the first device it is used on.  `may_allocate` = false: only
+// report whether the plan is resident here (nothing is allocated, ROSE_ERR_SCRATCH if it is not).
+rose_status device_tables(const rose_plan *p, bool may_allocate = true) {
     std::lock_guard<std::mutex> lock(p->mu);
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return ROSE_ERR_HIP;
     if (p->device == dev) return ROSE_OK;
     if (p->device != -1) return ROSE_ERR_ARG;
+    if (!may_allocate) return ROSE_ERR_SCRATCH;
 
     // elements of a shard's copy of each tensor, per receiving stage (0: the stage does not hold it)
     std::vector<int32_t> numel((size_t)p->pp_dst * p->n_tensors, 0);
@@ -40,6 +42,8 @@ rose_status device_tables(const rose_plan *p) {
     int64_t *drn = nullptr;
     unsigned long long *dv = nullptr;
     int resident[8];
+    void *sws = nullptr;
+    size_t sws_bytes = 0;
     const size_t pb = p->pieces.size() * sizeof(rose::Piece), tb = p->tile_piece.size() * sizeof(int32_t);
     const size_t nb = numel.size() * sizeof(int32_t), vb = kVerdictSlots * sizeof(unsigned long long);
     bool ok = hipMalloc(reinterpret_cast<void **>(&dp), pb) == hipSuccess &&
@@ -56,7 +60,7 @@ rose_status device_tables(const rose_plan *p) {
              hipMemcpy(dr, repl.data(), repl.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
              hipMemcpy(drn, repl_numel.data(), repl.size() * sizeof(int64_t), hipMemcpyHostToDevice) == hipSuccess;
     }
-    ok = ok && rose::encode_resident_all(resident) == 0;
+    ok = ok && rose::encode_resident_all(resident) == 0 && rose::static_scratch(&sws, &sws_bytes) == 0;
     if (!ok) {
         if (dp) (void)hipFree(dp);
         if (dt) (void)hipFree(dt);
@@ -74,6 +78,8 @@ rose_status device_tables(const rose_plan *p) {
     p->d_repl_numel = drn;
     p->n_repl = (int32_t)repl.size();
     std::memcpy(p->resident, resident, sizeof resident);
+    p->static_ws = sws;
+    p->static_ws_bytes = sws_bytes;
     p->device = dev;
     return ROSE_OK;
 }
@@ -103,10 +109,12 @@ extern "C" void rose_shard_plan_destroy(rose_plan *p) {
     delete p;
 }
 
+// workspace = nullptr: the library's built-in scratch (the call must not allocate)
 static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs, const void *const *new_ptrs,
                                  int32_t new_dtype, const rose_bucket *buckets, void *workspace,
                                  size_t workspace_bytes, bool refresh, bool arith, void *stream) {
-    if (!p || !old_ptrs || !new_ptrs || !buckets || !workspace) return ROSE_ERR_ARG;
+    const bool built_in = workspace == nullptr && workspace_bytes == (size_t)-1;
+    if (!p || !old_ptrs || !new_ptrs || !buckets || (!workspace && !built_in)) return ROSE_ERR_ARG;
     if (new_dtype != ROSE_BF16 && new_dtype != ROSE_FP32_RNE) return ROSE_ERR_ARG;
     size_t need = 0;
     rose_plan_workspace_bytes(p, &need);
@@ -121,8 +129,13 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
         a.bucket[d].capacity = buckets[d].capacity;
         a.bucket[d].seg_off = buckets[d].seg_off;
     }
-    rose_status s = device_tables(p);
+    rose_status s = device_tables(p, !built_in);
     if (s != ROSE_OK) return s;
+    if (built_in) {
+        if (need > p->static_ws_bytes) return ROSE_ERR_SCRATCH;
+        workspace = p->static_ws;
+        workspace_bytes = p->static_ws_bytes;
+    }
     if (workspace_bytes < need) return ROSE_ERR_ARG;
     if (!aligned(workspace, 256)) return ROSE_ERR_ALIGN;
     std::memcpy(a.chain_first, p->chain_first, sizeof a.chain_first);
@@ -170,6 +183,14 @@ extern "C" rose_status rose_delta_encode_ex(const rose_plan *p, void *const *old
     if (flags & ~(uint32_t)(ROSE_ENCODE_REFRESH | ROSE_ENCODE_ARITH)) return ROSE_ERR_ARG;
     return encode_common(p, const_cast<const void *const *>(old_ptrs), new_ptrs, new_dtype, buckets, workspace,
                          workspace_bytes, (flags & ROSE_ENCODE_REFRESH) != 0, (flags & ROSE_ENCODE_ARITH) != 0, stream);
+}
+
+extern "C" rose_status rose_delta_encode_static(const rose_plan *p, void *const *old_ptrs,
+                                                const void *const *new_ptrs, int32_t new_dtype, uint32_t flags,
+                                                const rose_bucket *buckets, void *stream) {
+    if (flags & ~(uint32_t)(ROSE_ENCODE_REFRESH | ROSE_ENCODE_ARITH)) return ROSE_ERR_ARG;
+    return encode_common(p, const_cast<const void *const *>(old_ptrs), new_ptrs, new_dtype, buckets, nullptr, (size_t)-1,
+                         (flags & ROSE_ENCODE_REFRESH) != 0, (flags & ROSE_ENCODE_ARITH) != 0, stream);
 }
 
 static rose_status apply_common(const rose_plan *p, int32_t d, const rose_bucket *bucket, int32_t payload,

@@ -7,6 +7,8 @@
 // kernel reads each weight once with 128-bit loads and writes only the changed entries.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "rose_internal.h"
 
 namespace rose {
@@ -1809,6 +1811,32 @@ int encode_resident_all(int resident[8]) {
         if (per_cu > ROSE_WGS_PER_CU) per_cu = ROSE_WGS_PER_CU;
         resident[v] = cus * per_cu;
     }
+    return 0;
+}
+
+// Built-in scratch for callers that cannot allocate (rose_delta_encode_static).  In host code the
+// array's name only stands for the symbol: its address on a device comes from hipGetSymbolAddress
+// with that device current, each device has its own copy, and only that pointer is ever handed to
+// a kernel.
+static __device__ __align__(256) unsigned long long scratch[ROSE_STATIC_SCRATCH_BYTES / sizeof(unsigned long long)];
+constexpr int kMaxDevices = 64;
+int static_scratch(void **ptr, size_t *bytes) {
+    static std::mutex mu;
+    static void *per_device[kMaxDevices] = {nullptr};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return (int)hipErrorInvalidValue;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    *bytes = sizeof(scratch);
     return 0;
 }
 

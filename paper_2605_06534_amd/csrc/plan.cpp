@@ -407,6 +407,9 @@ extern "C" const char *rose_status_str(rose_status s) {
     case ROSE_ERR_ALIGN: return "pointer not aligned";
     case ROSE_ERR_HIP: return "HIP runtime error";
     case ROSE_ERR_UNSUPPORTED: return "unsupported size";
+    case ROSE_ERR_SCRATCH:
+        return "the plan is not resident on this device (rose_plan_upload), or it needs more scratch than the "
+               "library's built-in buffer holds";
     }
     return "unknown status";
 }

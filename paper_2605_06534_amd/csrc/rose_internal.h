@@ -133,6 +133,9 @@ int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refres
 // resident workgroups of each of the eight encode kernel variants on the current device
 // (index: fp32 input + 2 * refresh + 4 * arithmetic payload)
 int encode_resident_all(int resident[8]);
+// Address and size of the library's built-in scratch array on the current device (one array per
+// device, found once per device with hipGetSymbolAddress and kept).
+int static_scratch(void **ptr, size_t *bytes);
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
                  int arith, void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
@@ -185,4 +188,6 @@ struct rose_plan {
     mutable int32_t n_repl = 0;
     mutable unsigned long long *d_verdict = nullptr;   // [kVerdictSlots]
     mutable int resident[8] = {0};             // see encode_resident_all
+    mutable void *static_ws = nullptr;         // the library's built-in scratch on `device`
+    mutable size_t static_ws_bytes = 0;
 };
