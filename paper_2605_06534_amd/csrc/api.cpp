@@ -204,7 +204,14 @@ static rose_status apply_common(const rose_plan *p, int32_t d, const rose_bucket
     s = device_tables(p);
     if (s != ROSE_OK) return s;
     const int32_t *local_numel = p->d_local_numel + (size_t)(d / p->tp) * p->n_tensors;
-    return rose::launch_apply(b, p->n_tensors, local_numel, dst_ptrs, payload, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
+    int64_t shard_elems = 0;
+    for (int32_t i = 0; i < p->n_tensors; ++i)
+        if (p->stage_dst_of[i] == d / p->tp) {
+            const rose_tensor_desc &t = p->tensors[i];
+            shard_elems += t.rows * t.cols / (t.rule == ROSE_REPLICATED ? 1 : p->tp);
+        }
+    return rose::launch_apply(b, p->n_tensors, local_numel, dst_ptrs, payload, shard_elems, stream) == 0 ? ROSE_OK
+                                                                                                       : ROSE_ERR_HIP;
 }
 
 extern "C" rose_status rose_delta_apply(const rose_plan *p, int32_t d, const rose_bucket *bucket,

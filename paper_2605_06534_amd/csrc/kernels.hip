@@ -1377,9 +1377,9 @@ __global__ __launch_bounds__(256) void refresh_replicated_kernel(const int32_t *
                              // (measured best on the 7B workload at 1 - 10 % density)
 #endif
 #ifndef ROSE_APPLY_BLOCKS
-#define ROSE_APPLY_BLOCKS (256 * 128)           // most workgroups an apply launch uses (7B workload, four shards:
-                                                // 2.33 / 5.01 ms at 1 / 5 % against 2.41 / 5.17 ms with 256 * 32;
-                                                // one workgroup per 256 entries is slower again at 10 %)
+#define ROSE_APPLY_BLOCKS (256 * 512)           // most workgroups an apply launch uses (7B workload, four shards, one
+                                                // chunk per wave: 2.40 / 3.64 / 4.92 ms at 1 / 2 / 5 % with 256 * 128,
+                                                // 2.36 / 3.48 / 4.51 ms with 256 * 512 or more)
 #endif
 constexpr int kApplyThreads = 256;
 constexpr int kApplyWaves = kApplyThreads / 64;
@@ -1390,10 +1390,11 @@ constexpr int kApplyWaves = kApplyThreads / 64;
                                                 // 64-byte units)
 #endif
 constexpr int kLineElems = ROSE_APPLY_LINE / 2; // line of 16-bit elements
-constexpr int kLineShift = ROSE_APPLY_LINE == 64 ? 5 : 4;
+constexpr int kLineShift = ROSE_APPLY_LINE == 128 ? 6 : ROSE_APPLY_LINE == 64 ? 5 : 4;
 constexpr int kLineParts = kLineElems / 8;      // 16-byte parts of a line
 constexpr int kLinesPerRound = 64 / kLineParts; // lines a wave moves with one load per lane
-static_assert(ROSE_APPLY_LINE == 64 || ROSE_APPLY_LINE == 32, "line size");
+static_assert(ROSE_APPLY_LINE == 128 || ROSE_APPLY_LINE == 64 || ROSE_APPLY_LINE == 32, "line size");
+
 
 __device__ __forceinline__ void lds_wave_fence() {
     // LDS operations of one wave are carried out in order; this keeps the compiler from moving
@@ -1425,136 +1426,239 @@ __device__ __forceinline__ uint16_t apply_value(uint32_t cur, uint32_t val, bool
 
 // arith != 0: the bucket holds arithmetic payloads (bit 31 of an index marks an entry that carries
 // the new pattern instead)
+//
+// The entries are cut into RUNS of chunks of 64, dealt round robin to the grid's waves, so that at any
+// time the waves work inside one band of the bucket that moves forward.  How long a run should be
+// depends on the density (measured on the 7B-style workload, 4 shards: runs of 1 / 8 chunks take
+// 2.36 / 2.58 ms at 1 %, 4.51 / 5.56 ms at 5 %, 7.30 / 6.0 ms at 10 %): where nearly every line of the
+// destination is touched, long runs make a wave stream through a contiguous piece of it; where the
+// touched lines lie apart, one chunk per wave and as many workgroups as there are chunks do best.  The
+// kernel picks the run length from the density it sees (entries against the elements of the shard).
+// Inside a run what a chunk needs from its neighbours is at hand: the next chunk's entries are
+// requested one chunk ahead (they are also the look-ahead for a line that straddles the two chunks),
+// the previous chunk's last index stays in a register, and the segment the wave is in (tensor, ends,
+// destination pointer, size) is uniform state that moves forward and is fetched with scalar loads.
+// All of a chunk's line loads are issued before the first is taken in.
+#ifndef ROSE_APPLY_RUN
+#define ROSE_APPLY_RUN 8        // chunks per run in the dense regime
+#endif
+#ifndef ROSE_APPLY_DENSE_DIV
+#define ROSE_APPLY_DENSE_DIV 13 // dense regime: at least one entry per this many elements of the shard
+#endif
+#ifndef ROSE_APPLY_DENSE_BLOCKS
+#define ROSE_APPLY_DENSE_BLOCKS (256 * 128)     // workgroups that take part in the dense regime
+#endif
+constexpr int kLineRounds = 64 / kLinesPerRound;     // rounds of one load per lane that move up to 64 lines
+// shard_elems: elements of the destination shard's tensors together (for the density estimate; objects,
+// which hold a part of a stream, pass a value that keeps them out of the dense regime)
 __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel,
-                                           void *const *dst_ptrs, int arith) {
+                                           void *const *dst_ptrs, int arith, int64_t shard_elems) {
     __shared__ uint4 s_line[kApplyWaves][64][kLineParts];   // wave, line slot, 16-byte part
     __shared__ u64 s_addr[kApplyWaves][64];             // address of the line
     __shared__ int32_t s_parts[kApplyWaves][64];        // 16-byte parts of the line inside the tensor
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t total = b.seg_off[n_tensors];
     if (total > b.capacity) total = b.capacity;
+    if (total <= 0) return;
+    const bool dense = total >= shard_elems / ROSE_APPLY_DENSE_DIV;
+    uint32_t n_wgs = gridDim.x;
+    if (dense && n_wgs > (uint32_t)ROSE_APPLY_DENSE_BLOCKS) n_wgs = ROSE_APPLY_DENSE_BLOCKS;
+    const uint32_t wg = blockIdx.x;
+    if (wg >= n_wgs) return;
+    const int64_t n_waves = (int64_t)n_wgs * kApplyWaves;
+    const int64_t run = dense ? (int64_t)ROSE_APPLY_RUN * 64 : 64;
+    const int32_t idx_mask = arith ? 0x7FFFFFFF : -1;
+    int32_t t_u = 0, t_have = -1, numel_u = 0;          // uniform: segment of the chunk's first entry, and the
+    int64_t seg_start_u = 0, seg_end_u = 0;             // tensor whose pointer and size are loaded
+    uint16_t *dst_u = nullptr;
 
-    for (int64_t wbase = ((int64_t)blockIdx.x * kApplyWaves + wave) * 64; wbase < total;
-         wbase += (int64_t)gridDim.x * kApplyThreads) {
-        const int64_t e = wbase + lane, e2 = e + 64;
-        const bool valid = e < total;
-        // everything that depends on the entry numbers alone is requested first
-        const int32_t idx_mask = arith ? 0x7FFFFFFF : -1;
+    for (int64_t rbase = ((int64_t)wg * kApplyWaves + wave) * run; rbase < total; rbase += n_waves * run) {
+        int64_t wbase = rbase;
+        const int64_t wend = rbase + run < total ? rbase + run : total;
+        if (wbase >= seg_end_u) {                       // (empty segments are stepped over by the search)
+            t_u = __builtin_amdgcn_readfirstlane(wave_find_segment(b.seg_off, n_tensors, wbase, lane));
+            seg_start_u = (int64_t)cload64(b.seg_off + t_u);
+            seg_end_u = (int64_t)cload64(b.seg_off + t_u + 1);
+        }
+        // the run's first chunk, and the last index before the run
+        int32_t cur_idx_raw = 0, prev_last = 0;
+        uint32_t cur_val = 0;
+        if (wbase + lane < total) {
 #if ROSE_APPLY_NT & 1
-        const int32_t idx_raw = valid ? __builtin_nontemporal_load(b.idx + e) : 0;
-        const uint32_t val = valid ? __builtin_nontemporal_load(b.val + e) : 0u;
+            cur_idx_raw = __builtin_nontemporal_load(b.idx + wbase + lane);
+            cur_val = __builtin_nontemporal_load(b.val + wbase + lane);
 #else
-        const int32_t idx_raw = valid ? b.idx[e] : 0;
-        const uint32_t val = valid ? b.val[e] : 0u;
-#endif
-        const int32_t idx_before = ((lane == 0 && wbase > 0) ? b.idx[wbase - 1] : 0) & idx_mask;
-        const bool look = lane < kLineElems && e2 < total;
-        const int32_t idx2_raw = look ? b.idx[e2] : 0;
-        const uint32_t val2 = look ? b.val[e2] : 0u;
-        const int32_t idx = idx_raw & idx_mask, idx2 = idx2_raw & idx_mask;
-        const bool add = arith && idx_raw >= 0, add2 = arith && idx2_raw >= 0;
-
-        // tensor of the wave's first entry, then of each lane's entry
-        int32_t t = wave_find_segment(b.seg_off, n_tensors, wbase, lane);
-        const int64_t seg_start0 = b.seg_off[t];
-        int64_t seg_end = b.seg_off[t + 1];
-        while (valid && e >= seg_end) {
-            ++t;
-            seg_end = b.seg_off[t + 1];
-        }
-        uint16_t *dst = valid ? static_cast<uint16_t *>(dst_ptrs[t]) : nullptr;
-        const int32_t numel = valid ? local_numel[t] : 0;
-        // may this entry go through the line path?  (depends on the entry alone)
-        const bool ok = valid && (((uintptr_t)dst) & 15u) == 0 && idx >= 0 && (idx | 7) < numel;
-        const u64 key = valid ? (((u64)(uint32_t)t << 32) | (uint32_t)(idx >> kLineShift)) : ~0ull;
-
-        // same line as the entry before?  lane 0 looks at the last entry of the previous chunk
-        u64 prev_key = __shfl_up(key, 1, 64);
-        if (lane == 0)
-            prev_key = wbase > seg_start0 ? (((u64)(uint32_t)t << 32) | (uint32_t)(idx_before >> kLineShift)) : ~0ull - 1;
-        const bool same = valid && key == prev_key;
-        // leading lanes that continue the previous chunk's last line belong to the previous wave
-        const u64 not_same = __ballot(!same);
-        const int first_own = not_same ? __ffsll((long long)not_same) - 1 : 64;
-        const bool owned = ok && lane >= first_own;
-        const bool direct = valid && !ok && idx >= 0 && idx < numel;   // an index outside the tensor is dropped
-
-        // entries of the next chunk that still lie in this chunk's last line
-        const u64 key63 = __shfl(key, 63, 64);
-        const bool own63 = __shfl((int)owned, 63, 64) != 0;
-        const int64_t seg_end63 = __shfl(seg_end, 63, 64);
-        const int32_t numel63 = __shfl(numel, 63, 64);
-        const bool ext = own63 && look && e2 < seg_end63 &&
-                         ((key63 & ~0xffffffffull) | (uint32_t)(idx2 >> kLineShift)) == key63 && idx2 >= 0 &&
-                         (idx2 | 7) < numel63;
-
-        // distinct lines of the owned entries
-        const bool prev_owned = __shfl_up((int)owned, 1, 64) != 0 && lane > 0;
-        const bool head = owned && (!prev_owned || !same);
-        const u64 heads = __ballot(head);
-        const int n_lines = __popcll(heads);
-        const int slot = __popcll(heads & ((2ull << lane) - 1)) - 1;      // line slot of an owned lane
-        if (head) {
-            const int32_t line_first = (idx >> kLineShift) << kLineShift;
-            s_addr[wave][slot] = (u64)(uintptr_t)(dst + line_first);
-            int32_t parts = (numel - line_first) >> 3;
-            s_parts[wave][slot] = parts > kLineParts ? kLineParts : parts;
-        }
-        lds_wave_fence();
-
-        // load the lines: kLineParts lanes per line, kLinesPerRound lines per round
-        for (int r = 0; r * kLinesPerRound < n_lines; ++r) {
-            const int sl = r * kLinesPerRound + lane / kLineParts, part = lane % kLineParts;
-            if (sl < n_lines && part < s_parts[wave][sl])
-#if ROSE_APPLY_NT & 2
-                s_line[wave][sl][part] = gload16_stream(reinterpret_cast<const char *>((uintptr_t)s_addr[wave][sl]) + part * 16);
-#else
-                s_line[wave][sl][part] = gload16(reinterpret_cast<const char *>((uintptr_t)s_addr[wave][sl]) + part * 16);
+            cur_idx_raw = b.idx[wbase + lane];
+            cur_val = b.val[wbase + lane];
 #endif
         }
-        lds_wave_fence();
+        if (wbase > 0) prev_last = b.idx[wbase - 1] & idx_mask;
 
-        // patch
-        uint16_t *lines16 = reinterpret_cast<uint16_t *>(&s_line[wave][0][0]);
-        if (owned) {
-            uint16_t *q = lines16 + slot * kLineElems + (idx & (kLineElems - 1));
-            *q = apply_value(*q, val, add);
-        }
-        if (ext) {
-            uint16_t *q = lines16 + (n_lines - 1) * kLineElems + (idx2 & (kLineElems - 1));
-            *q = apply_value(*q, val2, add2);
-        }
-        lds_wave_fence();
+        for (;;) {
+            const int64_t e = wbase + lane, e2 = e + 64;
+            const bool valid = e < total;
+            // the next chunk's entries: requested now, needed as look-ahead below and as the entries
+            // of the next round (the run's last chunk only looks into them)
+            int32_t nxt_idx_raw = 0;
+            uint32_t nxt_val = 0;
+            if (e2 < total) {
+#if ROSE_APPLY_NT & 1
+                nxt_idx_raw = __builtin_nontemporal_load(b.idx + e2);
+                nxt_val = __builtin_nontemporal_load(b.val + e2);
+#else
+                nxt_idx_raw = b.idx[e2];
+                nxt_val = b.val[e2];
+#endif
+            }
+            const int32_t idx_raw = cur_idx_raw;
+            const uint32_t val = cur_val;
+            const bool look = lane < kLineElems && e2 < total;
+            const int32_t idx2_raw = look ? nxt_idx_raw : 0;
+            const uint32_t val2 = look ? nxt_val : 0u;
+            const int32_t idx = idx_raw & idx_mask, idx2 = idx2_raw & idx_mask;
+            const bool add = arith && idx_raw >= 0, add2 = arith && idx2_raw >= 0;
 
-        // store the lines back whole
-        for (int r = 0; r * kLinesPerRound < n_lines; ++r) {
-            const int sl = r * kLinesPerRound + lane / kLineParts, part = lane % kLineParts;
-            if (sl < n_lines && part < s_parts[wave][sl])
-#if ROSE_APPLY_NT & 4
-                {
-                    const uint4 v4 = s_line[wave][sl][part];
-                    u32x4 w = {v4.x, v4.y, v4.z, v4.w};
-                    __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>((uintptr_t)s_addr[wave][sl] + part * 16));
+            // tensor of the chunk's first entry, then of each lane's entry
+            while (wbase >= seg_end_u) {                // ends: wbase < total <= seg_off[n_tensors]
+                ++t_u;
+                seg_start_u = seg_end_u;
+                seg_end_u = (int64_t)cload64(b.seg_off + t_u + 1);
+            }
+            int32_t t = t_u;
+            int64_t seg_end = seg_end_u;
+            uint16_t *dst;
+            int32_t numel;
+            const int64_t chunk_last = wbase + 63 < total ? wbase + 63 : total - 1;
+            if (chunk_last < seg_end_u) {               // the whole chunk lies in one segment: all uniform
+                if (t_have != t_u) {
+                    dst_u = reinterpret_cast<uint16_t *>(cload64(dst_ptrs + t_u));
+                    numel_u = (int32_t)cload32(local_numel + t_u);
+                    t_have = t_u;
                 }
+                dst = valid ? dst_u : nullptr;
+                numel = valid ? numel_u : 0;
+            } else {
+                while (valid && e >= seg_end) {
+                    ++t;
+                    seg_end = b.seg_off[t + 1];
+                }
+                dst = valid ? static_cast<uint16_t *>(dst_ptrs[t]) : nullptr;
+                numel = valid ? local_numel[t] : 0;
+            }
+            // may this entry go through the line path?  (depends on the entry alone)
+            const bool ok = valid && (((uintptr_t)dst) & 15u) == 0 && idx >= 0 && (idx | 7) < numel;
+            const u64 key = valid ? (((u64)(uint32_t)t << 32) | (uint32_t)(idx >> kLineShift)) : ~0ull;
+
+            // same line as the entry before?  lane 0 looks at the last entry of the previous chunk
+            u64 prev_key = __shfl_up(key, 1, 64);
+            if (lane == 0)
+                prev_key = wbase > seg_start_u ? (((u64)(uint32_t)t << 32) | (uint32_t)(prev_last >> kLineShift)) : ~0ull - 1;
+            const bool same = valid && key == prev_key;
+            // leading lanes that continue the previous chunk's last line were applied with that chunk
+            const u64 not_same = __ballot(!same);
+            const int first_own = not_same ? __ffsll((long long)not_same) - 1 : 64;
+            const bool owned = ok && lane >= first_own;
+            const bool direct = valid && !ok && idx >= 0 && idx < numel;   // an index outside the tensor is dropped
+
+            // entries of the next chunk that still lie in this chunk's last line
+            const u64 key63 = __shfl(key, 63, 64);
+            const bool own63 = __shfl((int)owned, 63, 64) != 0;
+            const int64_t seg_end63 = __shfl(seg_end, 63, 64);
+            const int32_t numel63 = __shfl(numel, 63, 64);
+            const bool ext = own63 && look && e2 < seg_end63 &&
+                             ((key63 & ~0xffffffffull) | (uint32_t)(idx2 >> kLineShift)) == key63 && idx2 >= 0 &&
+                             (idx2 | 7) < numel63;
+
+            // distinct lines of the owned entries
+            const bool prev_owned = __shfl_up((int)owned, 1, 64) != 0 && lane > 0;
+            const bool head = owned && (!prev_owned || !same);
+            const u64 heads = __ballot(head);
+            const int n_lines = __popcll(heads);
+            const int slot = __popcll(heads & ((2ull << lane) - 1)) - 1;      // line slot of an owned lane
+            if (head) {
+                const int32_t line_first = (idx >> kLineShift) << kLineShift;
+                s_addr[wave][slot] = (u64)(uintptr_t)(dst + line_first);
+                int32_t parts = (numel - line_first) >> 3;
+                s_parts[wave][slot] = parts > kLineParts ? kLineParts : parts;
+            }
+            lds_wave_fence();
+
+            // load the lines: kLineParts lanes per line, kLinesPerRound lines per round; every
+            // round's load is issued before the first one is put into LDS
+            const int part = lane % kLineParts;
+            uint4 lv[kLineRounds];
+            u64 la[kLineRounds];
+            bool on[kLineRounds];
+#pragma unroll
+            for (int r = 0; r < kLineRounds; ++r) {
+                const int sl = r * kLinesPerRound + lane / kLineParts;
+                on[r] = sl < n_lines && part < s_parts[wave][sl];
+                la[r] = on[r] ? s_addr[wave][sl] + (u64)(part * 16) : 0;
+            }
+#pragma unroll
+            for (int r = 0; r < kLineRounds; ++r) {
+                lv[r] = make_uint4(0, 0, 0, 0);
+                if (on[r]) {
+#if ROSE_APPLY_NT & 2
+                    lv[r] = gload16_stream(reinterpret_cast<const void *>((uintptr_t)la[r]));
 #else
-                gstore16(reinterpret_cast<char *>((uintptr_t)s_addr[wave][sl]) + part * 16, s_line[wave][sl][part]);
+                    lv[r] = gload16(reinterpret_cast<const void *>((uintptr_t)la[r]));
 #endif
-        }
-        if (direct) {
-            const uint16_t v = apply_value(add ? dst[idx] : 0u, val, add);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < kLineRounds; ++r)
+                if (on[r]) s_line[wave][r * kLinesPerRound + lane / kLineParts][part] = lv[r];
+            lds_wave_fence();
+
+            // patch
+            uint16_t *lines16 = reinterpret_cast<uint16_t *>(&s_line[wave][0][0]);
+            if (owned) {
+                uint16_t *q = lines16 + slot * kLineElems + (idx & (kLineElems - 1));
+                *q = apply_value(*q, val, add);
+            }
+            if (ext) {
+                uint16_t *q = lines16 + (n_lines - 1) * kLineElems + (idx2 & (kLineElems - 1));
+                *q = apply_value(*q, val2, add2);
+            }
+            lds_wave_fence();
+
+            // store the lines back whole
+#pragma unroll
+            for (int r = 0; r < kLineRounds; ++r) {
+                if (on[r]) {
+                    const uint4 v4 = s_line[wave][r * kLinesPerRound + lane / kLineParts][part];
+#if ROSE_APPLY_NT & 4
+                    u32x4 w = {v4.x, v4.y, v4.z, v4.w};
+                    __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>((uintptr_t)la[r]));
+#else
+                    gstore16(reinterpret_cast<void *>((uintptr_t)la[r]), v4);
+#endif
+                }
+            }
+            if (direct) {
+                const uint16_t v = apply_value(add ? dst[idx] : 0u, val, add);
 #if ROSE_APPLY_NT & 8
-            __builtin_nontemporal_store(v, dst + idx);
+                __builtin_nontemporal_store(v, dst + idx);
 #else
-            dst[idx] = v;
+                dst[idx] = v;
 #endif
+            }
+            lds_wave_fence();                           // the LDS slots are reused by the next chunk
+
+            wbase += 64;
+            if (wbase >= wend) break;
+            prev_last = __builtin_amdgcn_readlane(idx, 63); // the chunk was full: another one follows
+            cur_idx_raw = nxt_idx_raw;
+            cur_val = nxt_val;
         }
-        lds_wave_fence();                               // the LDS slots are reused by the next round
     }
 }
 
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(BucketDev b, int32_t n_tensors,
-                                                              const int32_t *local_numel, void *const *dst_ptrs, int arith) {
-    apply_body(b, n_tensors, local_numel, dst_ptrs, arith);
+                                                              const int32_t *local_numel, void *const *dst_ptrs, int arith,
+                                                              int64_t shard_elems) {
+    apply_body(b, n_tensors, local_numel, dst_ptrs, arith, shard_elems);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1680,7 +1784,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_object_kernel(const char 
     if (*verdict == ticket) return;                                    // the validation pass found it out of order
     const BucketDev b = object_arrays(obj, n_tensors, n);
     if (b.seg_off[0] != 0 || b.seg_off[n_tensors] != n) return;
-    apply_body(b, n_tensors, local_numel + (size_t)(h[2] / (uint32_t)tp) * n_tensors, dst_ptrs, (int)h[8]);
+    apply_body(b, n_tensors, local_numel + (size_t)(h[2] / (uint32_t)tp) * n_tensors, dst_ptrs, (int)h[8], INT64_MAX);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1888,11 +1992,12 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *ref
 }
 
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
-                 int arith, void *stream) {
+                 int arith, int64_t shard_elems, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t chunks = (b.capacity + kApplyThreads - 1) / kApplyThreads;
     int blocks = chunks < 1 ? 1 : (chunks > ROSE_APPLY_BLOCKS ? ROSE_APPLY_BLOCKS : (int)chunks);
-    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs, arith);
+    hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(kApplyThreads), 0, st, b, n_tensors, local_numel, dst_ptrs, arith,
+                       shard_elems);
     return (int)hipGetLastError();
 }
 

@@ -136,8 +136,10 @@ int encode_resident_all(int resident[8]);
 // Address and size of the library's built-in scratch array on the current device (one array per
 // device, found once per device with hipGetSymbolAddress and kept).
 int static_scratch(void **ptr, size_t *bytes);
+// shard_elems: elements of the destination shard's tensors together (the kernel compares the entry
+// count with it to choose how it walks the entries)
 int launch_apply(const BucketDev &b, int32_t n_tensors, const int32_t *local_numel, void *const *dst_ptrs,
-                 int arith, void *stream);
+                 int arith, int64_t shard_elems, void *stream);
 int launch_dense_copy(const CopyArgs &a, int new_is_f32, void *stream);
 int launch_pack(const BucketDev &b, int32_t shard, int32_t n_tensors, int64_t first, int64_t n, int32_t payload,
                 void *object, void *stream);
