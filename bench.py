@@ -260,13 +260,14 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
     gc.collect()
     torch.cuda.empty_cache()
     if probes:
-        res["bw_probe"] = bw_probes(R, nnz_total, n_tiles, new_dtype == R.BF16)
+        res["bw_probe"] = bw_probes(R, nnz_total, n_tiles, new_dtype == R.BF16, 1 - (1 - dens) ** 32)
     return res
 
 
-def bw_probes(R, nnz_total, n_tiles, mixed):
-    """What HBM delivers beside the kernels, in the same run: 1 GiB copy and read, and (bf16 input)
-    a stream with the encode launch's mix of reads and writes and none of its work."""
+def bw_probes(R, nnz_total, n_tiles, mixed, touched_lines):
+    """What HBM delivers beside the kernels, in the same run: 1 GiB copy and read, a read-modify-write
+    of the share of 64-byte lines that apply touches at this density (4 GiB, no other work), and
+    (bf16 input) a stream with the encode launch's mix of reads and writes and none of its work."""
     dev = torch.device("cuda:0")
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
     dst = torch.empty_like(src)
@@ -284,6 +285,18 @@ def bw_probes(R, nnz_total, n_tiles, mixed):
         moved = (2 if name == "copy" else 1) * src.numel() * 10
         probe[name + "_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
     del src, dst
+    lines = torch.zeros(4 << 30, dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        R.bw_probe_lines(lines, touched_lines)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        R.bw_probe_lines(lines, touched_lines)
+    b.record()
+    torch.cuda.synchronize()
+    probe["lines_rmw_GBs"] = round(2 * touched_lines * lines.numel() * 5 / 1e9 / (a.elapsed_time(b) / 1e3), 1)
+    probe["lines_rmw_touched_share"] = round(touched_lines, 4)
+    del lines
     if mixed:
         # two read streams, 6 * nnz / tiles bytes written per 2 x 16 KB read
         per_chunk = min(16384, max(16, int(round(6 * nnz_total / max(n_tiles, 1) / 16)) * 16))

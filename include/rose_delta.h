@@ -178,6 +178,20 @@ rose_status rose_plan_upload(const rose_plan *plan);
  * it finds.
  */
 rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
+/*
+ * The order in which the encode kernel's workgroups take tiles (it changes speed only: the buckets
+ * are the same bytes either way).  ROSE_TILE_ORDER_SPREAD: a workgroup takes tiles that lie 64 tiles
+ * apart, so that the prefix sums across workgroups are ready soonest; best above about 6 % of changed
+ * elements.  ROSE_TILE_ORDER_NEIGHBOURS: it takes three neighbouring tiles and writes their entries
+ * as one run, which shares fewer 64-byte lines of the bucket with other workgroups; best at low
+ * densities.  ROSE_TILE_ORDER_AUTO_PICK (the default): the library picks, from the density of the
+ * plan's previous launch as far as rose_bucket_check has read it back (spread until then).
+ * May be called at any time from any thread; a launch uses the value it finds.
+ */
+#define ROSE_TILE_ORDER_AUTO_PICK 0
+#define ROSE_TILE_ORDER_SPREAD 1
+#define ROSE_TILE_ORDER_NEIGHBOURS 2
+rose_status rose_plan_set_tile_order(rose_plan *plan, int32_t order);
 
 /* Host queries on a plan (no GPU needed). */
 int32_t rose_plan_n_tensors(const rose_plan *plan);
@@ -338,6 +352,7 @@ rose_status rose_dense_copy(const rose_plan *plan, int32_t d, const void *const 
 /*
  * Synchronises `stream`, reads seg_off[n_tensors] of the bucket back and returns
  * ROSE_ERR_CAPACITY if it exceeds capacity.  *required (host, may be NULL) gets the count.
+ * The plan remembers the density that the count implies (see rose_plan_set_tile_order).
  */
 rose_status rose_bucket_check(const rose_plan *plan, const rose_bucket *bucket, void *stream,
                               int64_t *required);
@@ -406,6 +421,15 @@ rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *si
 #define ROSE_PROBE_CHUNK 16384
 rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
                                 size_t write_bytes_per_chunk, uint64_t *sink, void *stream);
+
+/*
+ * Line probe: what HBM delivers for delta_apply's access pattern without any of its work.  Reads,
+ * changes and writes back a pseudo-random subset of the 64-byte lines of dst (device, 64-byte aligned,
+ * `bytes` a multiple of 64): line i is touched if a fixed hash of i is below touched_per_2_32, i.e.
+ * about that fraction / 2^32 of the lines, independently.  Every 32-bit word at the start of a
+ * 16-byte part of a touched line is incremented; nothing else changes.
+ */
+rose_status rose_bw_probe_lines(void *dst, size_t bytes, uint32_t touched_per_2_32, void *stream);
 
 const char *rose_status_str(rose_status s);
 

@@ -7,7 +7,7 @@ loudly if it is not built (there is no CPU fallback)."""
 import importlib
 
 __all__ = ["BF16", "FP32_RNE", "FUSED_ROWS", "REPLICATED", "SPLIT_COLS", "SPLIT_ROWS", "LAYER_FIRST", "LAYER_LAST",
-           "Bucket", "Plan", "RoseError", "bucket_check", "bw_probe", "bw_probe_mixed", "delta_apply", "delta_encode",
+           "Bucket", "Plan", "RoseError", "bucket_check", "bw_probe", "bw_probe_mixed", "bw_probe_lines", "delta_apply", "delta_encode",
            "delta_encode_refresh", "dense_copy", "ENCODE_ARITH", "ENCODE_REFRESH", "PAYLOAD_ARITH", "PAYLOAD_NEW",
            "delta_encode_ex", "delta_encode_static", "delta_apply_ex", "bucket_pack_ex", "bucket_pack", "object_apply",
            "object_bytes", "object_check", "ptr_table", "shard_plan", "workspace", "binding"]

@@ -16,6 +16,7 @@ REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
 BF16, FP32_RNE = 0, 1
 OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED, ERR_SCRATCH = range(8)
 LAYER_FIRST, LAYER_LAST = -1, -2
+TILE_ORDER_AUTO, TILE_ORDER_SPREAD, TILE_ORDER_NEIGHBOURS = 0, 1, 2
 STATIC_SCRATCH_BYTES = 48 << 20
 
 _LIB_PATH = os.environ.get("ROSE_DELTA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
@@ -45,6 +46,7 @@ _SIGS = {
     "rose_shard_plan_destroy": (None, [_vp]),
     "rose_plan_upload": (_i32, [_vp]),
     "rose_plan_set_worker_cap": (_i32, [_vp, _i32]),
+    "rose_plan_set_tile_order": (_i32, [_vp, _i32]),
     "rose_plan_n_tensors": (_i32, [_vp]),
     "rose_plan_tp": (_i32, [_vp]),
     "rose_plan_n_buckets": (_i32, [_vp]),
@@ -72,6 +74,7 @@ _SIGS = {
     "rose_object_check": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _P(_i32), _P(_i64), _P(_i64), _P(_i32)]),
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
     "rose_bw_probe_mixed": (_i32, [_vp, _vp, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp]),
+    "rose_bw_probe_lines": (_i32, [_vp, ctypes.c_size_t, ctypes.c_uint32, _vp]),
     "rose_status_str": (ctypes.c_char_p, [_i32]),
 }
 
@@ -137,6 +140,9 @@ class Plan:
 
     def set_worker_cap(self, workers):
         _check(_lib.rose_plan_set_worker_cap(self._h, workers), "plan_set_worker_cap")
+
+    def set_tile_order(self, order):
+        _check(_lib.rose_plan_set_tile_order(self._h, order), "plan_set_tile_order")
 
     def stage_of(self, t):
         a, b = _i32(), _i32()
@@ -313,6 +319,13 @@ def bw_probe_mixed(src_a, src_b, dst, write_bytes_per_chunk, sink, stream=None):
     nbytes = src_a.numel() * src_a.element_size()
     _check(_lib.rose_bw_probe_mixed(src_a.data_ptr(), src_b.data_ptr(), dst.data_ptr(), nbytes,
                                     write_bytes_per_chunk, sink.data_ptr(), _stream(stream)), "bw_probe_mixed")
+
+
+def bw_probe_lines(dst, touched_fraction, stream=None):
+    """read-modify-write of about `touched_fraction` of the 64-byte lines of dst"""
+    thr = min(0xFFFFFFFF, max(0, int(round(touched_fraction * 4294967296.0))))
+    _check(_lib.rose_bw_probe_lines(dst.data_ptr(), dst.numel() * dst.element_size(), thr, _stream(stream)),
+           "bw_probe_lines")
 
 
 def object_bytes(plan, n_entries):

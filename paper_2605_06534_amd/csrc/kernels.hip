@@ -483,7 +483,7 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 #define ROSE_RING 8192
 #endif
 #ifndef ROSE_QUEUE
-#define ROSE_QUEUE 16
+#define ROSE_QUEUE 32         // (16 to 64 measure the same; the neighbours order parks about twice as many tiles)
 #endif
 constexpr int kRing = ROSE_RING;        // entries parked per workgroup (power of two)
 constexpr int kQueue = ROSE_QUEUE;      // tiles parked per workgroup (<= 64)
@@ -491,6 +491,8 @@ static_assert((kRing & (kRing - 1)) == 0 && (kQueue & (kQueue - 1)) == 0 && kQue
               "ring and queue sizes must be powers of two, the queue at most a wave");
 
 enum : int { kLoadVec = 0, kLoadGeneral = 1 };
+enum : int { kDrainOldest = 0, kDrainAll = 1, kDrainReady = 2 };
+
 
 struct TileCtx {
     Piece pc;
@@ -584,16 +586,32 @@ __device__ __forceinline__ void load_raw_pair(const TileCtx &c, uint32_t t_off, 
     }
 }
 
-// Tile at position (ticket mod kBlock) of block (ticket / kBlock) * kBatch + j, or -1 if that block
-// does not exist or is a chain's short last block without that position.  Uniform.
+// The j-th tile of a ticket, or -1 if there is none.  A group of kBatch consecutive blocks has
+// kBatch * kBlock tile positions ("slots", block after block) and kBlock tickets.  Two orders:
+// spread (a.adjacent = 0): ticket n of the group stands for position n of each of the group's blocks, so
+// that a block's 64 tiles are walked by 64 workers at once and its prefixes are ready one tile-time
+// later; neighbours (a.adjacent = 1): ticket n stands for the kBatch NEIGHBOURING slots
+// n * kBatch .. n * kBatch + kBatch - 1.  Neighbouring slots are
+// neighbouring tiles of one chain (except where a chain ends inside the group: a chain's short last
+// block has no tile for its last positions), so the entries of a ticket's tiles follow each other in
+// the bucket and are written as one run: only the two ends of a ticket's run share 64-byte lines of
+// the bucket with another workgroup's.  (Measured on the 7B-style workload with every run padded to
+// whole lines, which is what no shared lines at all would give: 3 % faster at 1 - 5 %, 7 % at 10 %.)
+// The price: a block's prefixes are ready kBatch tile-times later, so more entries wait in the ring,
+// which pays while the ring holds them (see launch_encode for who picks the order).  Uniform.
 __device__ __forceinline__ int32_t ticket_tile(const EncodeArgs &a, int32_t ticket, int32_t j) {
     ticket = __builtin_amdgcn_readfirstlane(ticket);    // uniform anyway: keeps the table look-ups scalar
     j = __builtin_amdgcn_readfirstlane(j);
-    const int32_t blk = (ticket / kBlock) * kBatch + j;
+    int32_t blk = (ticket / kBlock) * kBatch + j, pos = ticket & (kBlock - 1);
+    if (a.adjacent) {
+        const int32_t slot = (ticket & (kBlock - 1)) * kBatch + j;
+        blk = (ticket / kBlock) * kBatch + slot / kBlock;
+        pos = slot & (kBlock - 1);
+    }
     if (blk >= a.n_blocks) return -1;
     int32_t shard = 0;
     while (blk >= a.block_first[shard + 1]) ++shard;
-    const int32_t t = a.chain_first[shard] + (blk - a.block_first[shard]) * kBlock + (ticket & (kBlock - 1));
+    const int32_t t = a.chain_first[shard] + (blk - a.block_first[shard]) * kBlock + pos;
     return t < a.chain_first[shard + 1] ? t : -1;
 }
 
@@ -712,59 +730,100 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     int n_polled = 0;           // lanes of wave 0 whose tiles the poll in flight covers
     bool ticket_out = false;    // a ticket has been asked for and not yet taken in
 
-    // copy the n oldest parked tiles to the buckets (prefixes in excl[0..n)); returns ring entries freed
+    // copy the n oldest parked tiles to the buckets (prefixes in excl[0..n)); returns ring entries freed.
+    // Tiles that follow each other in the bucket (up to four: same shard, each starting where the one
+    // before ends; their entries follow each other in the ring as well) are written as one run.
     auto copy_out = [&](int n, const u64 *excl_by_age, bool ok) -> uint32_t {
         uint32_t freed = 0;
-        for (int i = 0; i < n; ++i) {
+        for (int i = 0; i < n;) {
             const int slot = (q_head + i) & (kQueue - 1);
-            // everything about the tile is uniform: kept in scalar registers, the bucket's
+            // everything about the tiles is uniform: kept in scalar registers, the bucket's
             // pointers come through scalar loads
-            const uint32_t cnt = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_count[slot]);
-            freed += cnt;
-            if (ok && !(ROSE_DIAG & 2)) {
-                const u64 excl = ((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(excl_by_age[i] >> 32)) << 32) |
-                                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)excl_by_age[i]);
-                const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_off[slot]);
-                const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_base[slot]);
-                const BucketDev b = a.bucket[__builtin_amdgcn_readfirstlane(s_q_shard[slot])];
-                const int32_t seg = __builtin_amdgcn_readfirstlane(s_q_seg[slot]);
-                const int32_t last = __builtin_amdgcn_readfirstlane(s_q_last[slot]);
+            const uint32_t cnt0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_count[slot]);
+            if (!ok || (ROSE_DIAG & 2)) {
+                freed += cnt0;
+                ++i;
+                continue;
+            }
+            const u64 excl = ((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(excl_by_age[i] >> 32)) << 32) |
+                             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)excl_by_age[i]);
+            const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_off[slot]);
+            const int32_t shard = __builtin_amdgcn_readfirstlane(s_q_shard[slot]);
+            const BucketDev b = a.bucket[shard];
+            const int32_t piece = __builtin_amdgcn_readfirstlane(s_q_piece[slot]);
+            // the run: this tile and the parked tiles behind it that continue it (c1..c3: where the
+            // second to fourth tile's entries start inside the run; b0..b3: see TileMeta::out_base)
+            uint32_t cnt = cnt0, c1 = 0xFFFFFFFFu, c2 = 0xFFFFFFFFu, c3 = 0xFFFFFFFFu;
+            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_base[slot]);
+            uint32_t b1 = 0, b2 = 0, b3 = 0;
+            int g = 1;
+            if (threadIdx.x == 0) {
+                const int32_t seg = s_q_seg[slot];
+                if (seg >= 0) b.seg_off[seg] = (int64_t)excl;
+                if (s_q_last[slot]) b.seg_off[a.n_tensors] = (int64_t)(excl + cnt0);
+            }
+            while (piece < 0 && g < 4 && i + g < n) {
+                const int s2 = (q_head + i + g) & (kQueue - 1);
+                const u64 e2 = ((u64)(uint32_t)__builtin_amdgcn_readfirstlane((int)(excl_by_age[i + g] >> 32)) << 32) |
+                               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)excl_by_age[i + g]);
+                if (__builtin_amdgcn_readfirstlane(s_q_shard[s2]) != shard || e2 != excl + cnt ||
+                    __builtin_amdgcn_readfirstlane(s_q_piece[s2]) >= 0)
+                    break;
+                const uint32_t cg = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_count[s2]);
+                const uint32_t bg = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_q_base[s2]);
                 if (threadIdx.x == 0) {
-                    if (seg >= 0) b.seg_off[seg] = (int64_t)excl;
-                    if (last) b.seg_off[a.n_tensors] = (int64_t)(excl + cnt);
+                    const int32_t seg = s_q_seg[s2];
+                    if (seg >= 0) b.seg_off[seg] = (int64_t)e2;
+                    if (s_q_last[s2]) b.seg_off[a.n_tensors] = (int64_t)(e2 + cg);
                 }
-                const int32_t piece = __builtin_amdgcn_readfirstlane(s_q_piece[slot]);
-                // local index of the element at offset o of the tile
-                uint32_t l_base = base, l_run = 0, l_magic = 0, l_shift = 0, l_stride = 0;
-                if (piece >= 0) {                      // the piece's local indices come in strided runs
-                    const Piece pc = load_piece(a.pieces + piece);
-                    l_base = (uint32_t)pc.local_base;
-                    l_run = (uint32_t)pc.run;
-                    l_magic = pc.magic;
-                    l_shift = pc.shift;
-                    l_stride = (uint32_t)pc.lstride;
-                }
-                for (uint32_t k = threadIdx.x; k < cnt; k += kThreads) {
-                    const u64 pos = excl + k;
-                    if (pos < (u64)b.capacity) {
-                        const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
-                        uint32_t local = base + (ARITH ? (entry >> 16) & (uint32_t)(kTile - 1) : entry >> 16);
-                        if (piece >= 0) {              // base is the tile's first element number here
-                            // (runs of one element have no magic divisor: the quotient is the number itself)
-                            const uint32_t q = l_run == 1u ? local : (__umulhi(local, l_magic) >> l_shift);
-                            local = l_base + q * l_stride + (local - q * l_run);
-                        }
-                        if constexpr (ARITH) local |= entry & 0x80000000u;
-#if ROSE_NT_STORES
-                        __builtin_nontemporal_store((int32_t)local, b.idx + pos);
-                        __builtin_nontemporal_store((uint16_t)entry, b.val + pos);
+                if (g == 1) { c1 = cnt; b1 = bg; }
+                else if (g == 2) { c2 = cnt; b2 = bg; }
+                else { c3 = cnt; b3 = bg; }
+                cnt += cg;
+                ++g;
+            }
+            freed += cnt;
+            // local index of the element at offset o of the tile
+            uint32_t l_base = b0, l_run = 0, l_magic = 0, l_shift = 0, l_stride = 0;
+            if (piece >= 0) {                          // the piece's local indices come in strided runs
+                const Piece pc = load_piece(a.pieces + piece);
+                l_base = (uint32_t)pc.local_base;
+                l_run = (uint32_t)pc.run;
+                l_magic = pc.magic;
+                l_shift = pc.shift;
+                l_stride = (uint32_t)pc.lstride;
+            }
+#if ROSE_DIAG & 16
+            // timing experiment only (wrong buckets): every run starts and ends on a 128-byte boundary of
+            // the index stream (64 of the value stream), as if neighbouring runs never shared a line
+            const u64 excl_x = excl & ~(u64)31;
+            const uint32_t cnt_x = (cnt + 31u) & ~31u;
 #else
-                        b.idx[pos] = (int32_t)local;
-                        b.val[pos] = (uint16_t)entry;
+            const u64 excl_x = excl;
+            const uint32_t cnt_x = cnt;
 #endif
+            for (uint32_t k = threadIdx.x; k < cnt_x; k += kThreads) {
+                const u64 pos = excl_x + k;
+                if (pos < (u64)b.capacity) {
+                    const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
+                    const uint32_t base = k < c1 ? b0 : k < c2 ? b1 : k < c3 ? b2 : b3;
+                    uint32_t local = base + (ARITH ? (entry >> 16) & (uint32_t)(kTile - 1) : entry >> 16);
+                    if (piece >= 0) {                  // base is the tile's first element number here
+                        // (runs of one element have no magic divisor: the quotient is the number itself)
+                        const uint32_t q = l_run == 1u ? local : (__umulhi(local, l_magic) >> l_shift);
+                        local = l_base + q * l_stride + (local - q * l_run);
                     }
+                    if constexpr (ARITH) local |= entry & 0x80000000u;
+#if ROSE_NT_STORES
+                    __builtin_nontemporal_store((int32_t)local, b.idx + pos);
+                    __builtin_nontemporal_store((uint16_t)entry, b.val + pos);
+#else
+                    b.idx[pos] = (int32_t)local;
+                    b.val[pos] = (uint16_t)entry;
+#endif
                 }
             }
+            i += g;
         }
         return freed;
     };
@@ -780,7 +839,10 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     // Blocking drain, for when there is no room to park (or at the end): waits until the oldest
     // parked tile (all = false) or every parked tile (all = true) has its prefix, and copies out
     // every leading tile whose prefix is known; these include the announced ones.
-    auto drain = [&](bool all) {
+    // mode kDrainOldest / kDrainAll as described; kDrainReady waits for nothing: it looks once and
+    // copies out what has its prefix by now.
+    auto drain = [&](int mode) {
+        const bool all = mode == kDrainAll;
         __syncthreads();                               // parked entries visible; earlier copies done
         if (wave == 0) {
             bool ok = true;
@@ -791,7 +853,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 if (lane < q_len && !has_prefix(wq_w)) wq_w = desc_load(a.tile_desc + wq_tile);
                 const u64 unknown = __ballot(lane < q_len && !has_prefix(wq_w));
                 n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
-                if (all ? (n_ready == q_len) : (n_ready >= 1 || q_len == 0)) break;
+                if (mode == kDrainReady || (all ? (n_ready == q_len) : (n_ready >= 1 || q_len == 0))) break;
                 if (!keep_waiting(a.abort_flag, spins, lane)) {
                     ok = false;         // give up: drop everything that is parked
                     n_ready = q_len;
@@ -1112,16 +1174,27 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         // publishing, exactly as for a same-group pair (below).
         bool dense = false;
 #if ROSE_COUNT_AHEAD
-        if (__builtin_expect(ring_used + tile_total > (uint32_t)kRing && q_len < kBatch, 0))
-            dense = !walk.careful && !cur_redo && !walk.redo && !big && next_state == kWalkTile &&
-                    walk.ticket == ticket_before;      // the next tile is of the same ticket: not all of it is counted
+        // the next tile is of the same ticket: not all of the ticket is counted
+        const bool mid_ticket = !walk.careful && !cur_redo && !walk.redo && !big && next_state == kWalkTile &&
+                                walk.ticket == ticket_before;
+        if (a.adjacent) {
+            // A ticket's tiles are neighbours, so its uncounted tiles may lie in the very block whose
+            // prefixes a wait would be for: in the middle of a ticket nothing may wait at all.  First
+            // look, without waiting, whether prefixes have arrived since the last poll.
+            if (__builtin_expect(mid_ticket && (q_len == kQueue || ring_used + tile_total > (uint32_t)kRing), 0)) {
+                if (q_len > 0) drain(kDrainReady);
+                dense = q_len == kQueue || ring_used + tile_total > (uint32_t)kRing;
+            }
+        } else if (__builtin_expect(ring_used + tile_total > (uint32_t)kRing && q_len < kBatch, 0)) {
+            dense = mid_ticket;
+        }
 #endif
         const bool skip = walk.careful || dense;
         if (skip) {
         } else if (big) {
-            if (q_len > 0) drain(true);
+            if (q_len > 0) drain(kDrainAll);
         } else {
-            while (q_len == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(false);
+            while (q_len == kQueue || ring_used + tile_total > (uint32_t)kRing) drain(kDrainOldest);
         }
 
         const int32_t chain_last = a.chain_first[cur.shard + 1] - 1;
@@ -1314,7 +1387,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         cur_redo = nxt_redo;
         tile = next;
     }
-    while (q_len > 0) drain(true);
+    while (q_len > 0) drain(kDrainAll);
 }
 
 // The instantiations get their own register budgets: 4 waves per SIMD (128 VGPRs) fit the bf16
@@ -1884,6 +1957,40 @@ __global__ __launch_bounds__(256) void bw_mix_kernel(const uint4 *a, const uint4
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) atomicAdd(sink, 1ull);
 }
 
+// Line probe: the memory traffic of an apply launch without its work.  A wave takes 128 consecutive
+// lines of 64 bytes, 16 per round (4 lanes per line); the lines whose hash is below the threshold are
+// loaded (all loads first, non-temporal like apply's), changed and stored back.
+__device__ __forceinline__ uint32_t line_hash(size_t i) {
+    uint32_t x = (uint32_t)i * 0x9E3779B1u ^ (uint32_t)((uint64_t)i >> 32);
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+__global__ __launch_bounds__(256) void bw_lines_kernel(uint4 *dst, size_t n_lines, uint32_t threshold) {
+    const int lane = threadIdx.x & 63;
+    const size_t base = ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 128;
+    uint4 v[8];
+    bool on[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const size_t line = base + (size_t)(r * 16 + lane / 4);
+        on[r] = line < n_lines && line_hash(line) < threshold;
+        v[r] = make_uint4(0, 0, 0, 0);
+        if (on[r]) v[r] = gload16_stream(dst + line * 4 + (lane & 3));
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (on[r]) {
+            const size_t line = base + (size_t)(r * 16 + lane / 4);
+            u32x4 w = {v[r].x + 1u, v[r].y, v[r].z, v[r].w};
+            __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(dst + line * 4 + (lane & 3))));
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
@@ -1949,9 +2056,10 @@ int static_scratch(void **ptr, size_t *bytes) {
 #endif
 
 int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, int arith, int resident,
-                  int worker_cap, void *stream) {
+                  int worker_cap, int adjacent, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     EncodeArgs a = args;
+    a.adjacent = adjacent ? 1 : 0;
     if (resident < 1) return (int)hipErrorInvalidValue;
     // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
     // a quarter of what is resident.  They are the first workgroups of the grid, so they are
@@ -2052,6 +2160,15 @@ int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, vo
     else
         hipLaunchKernelGGL(bw_read_kernel, dim3(blocks), dim3(kBwThreads), 0, st,
                            static_cast<const uint4 *>(src), n16, reinterpret_cast<u64 *>(sink));
+    return (int)hipGetLastError();
+}
+
+int launch_bw_probe_lines(void *dst, size_t n_lines, uint32_t threshold, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_lines == 0) return 0;
+    const size_t blocks = (n_lines + 511) / 512;
+    if (blocks > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(bw_lines_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint4 *>(dst), n_lines, threshold);
     return (int)hipGetLastError();
 }
 

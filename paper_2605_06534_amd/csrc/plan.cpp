@@ -261,6 +261,7 @@ extern "C" rose_status rose_shard_plan_create_pp(const rose_tensor_desc *tensors
             }
         }
         for (int32_t b = p->n_buckets; b <= ROSE_MAX_TP; ++b) p->chain_first[b] = (int32_t)n_tiles;
+        for (const Piece &pc : p->pieces) p->capacity_sum += pc.len;
         int32_t n_blocks = 0;
         for (int32_t b = 0; b <= ROSE_MAX_TP; ++b) {
             p->block_first[b] = n_blocks;
@@ -307,6 +308,12 @@ extern "C" rose_status rose_plan_tensor_is_read(const rose_plan *p, int32_t t, u
     if (!p || !is_read || t < 0 || t >= p->n_tensors) return ROSE_ERR_ARG;
     if (flags & ~(uint32_t)(ROSE_ENCODE_REFRESH | ROSE_ENCODE_ARITH)) return ROSE_ERR_ARG;
     *is_read = tensor_is_read(p, t, flags) ? 1 : 0;
+    return ROSE_OK;
+}
+
+extern "C" rose_status rose_plan_set_tile_order(rose_plan *p, int32_t order) {
+    if (!p || order < ROSE_TILE_ORDER_AUTO_PICK || order > ROSE_TILE_ORDER_NEIGHBOURS) return ROSE_ERR_ARG;
+    p->tile_order.store(order, std::memory_order_relaxed);
     return ROSE_OK;
 }
 

@@ -83,6 +83,7 @@ struct EncodeArgs {
     int32_t n_server_wgs;                   // workgroups 0 .. n_server_wgs-1 serve prefixes, the rest walk tiles
     int32_t n_servers;                      // waves that serve prefixes (kWaves per serving workgroup)
     int32_t n_tickets;                      // tickets the counter hands out
+    int32_t adjacent;                       // a ticket's tiles are neighbours in the bucket (see ticket_tile)
     unsigned int *ticket;                   // workspace header: the ticket counter
 };
 
@@ -129,7 +130,7 @@ struct RefreshArgs {
 // resident: workgroups of this kernel variant that fit on the device at once (encode_resident_all);
 // worker_cap: 0, or the most workgroups that may walk tiles
 int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, int arith, int resident,
-                  int worker_cap, void *stream);
+                  int worker_cap, int adjacent, void *stream);
 // resident workgroups of each of the eight encode kernel variants on the current device
 // (index: fp32 input + 2 * refresh + 4 * arithmetic payload)
 int encode_resident_all(int resident[8]);
@@ -152,6 +153,7 @@ int launch_apply_object(const void *object, size_t object_bytes, int32_t n_tenso
 size_t object_bytes_for(int32_t n_tensors, int64_t n);
 bool object_header_valid(const uint32_t *header, int32_t n_tensors, size_t object_bytes, int64_t *n);
 int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
+int launch_bw_probe_lines(void *dst, size_t n_lines, uint32_t threshold, void *stream);
 int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, uint64_t *sink,
                           void *stream);
 
@@ -177,6 +179,10 @@ struct rose_plan {
     int32_t chain_first[ROSE_MAX_TP + 1] = {0};
     int32_t block_first[ROSE_MAX_TP + 1] = {0};
     mutable std::atomic<int32_t> worker_cap{0};     // rose_plan_set_worker_cap
+    mutable std::atomic<int32_t> tile_order{0};     // rose_plan_set_tile_order
+    mutable std::atomic<int32_t> seen_density_ppm{-1};   // changed elements per million as estimated from the last
+                                                         // bucket total that rose_bucket_check read back (-1: none yet)
+    int64_t capacity_sum = 0;                            // entries of all buckets together if every element changed
     mutable std::atomic<uint64_t> verdict_ticket{0};
     // device copies of pieces / tile_piece, made on first use on a device (the only device the plan is used on)
     mutable std::mutex mu;

@@ -27,3 +27,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(params=[1, 2], ids=["spread", "neighbours"])
+def tile_order(request, monkeypatch):
+    """Runs a test once per order in which the encode kernel's workgroups take tiles (the buckets
+    must be the same bytes either way): every plan the test makes gets the order set."""
+    from paper_2605_06534_amd import binding
+    make = binding.shard_plan
+
+    def planned(*a, **kw):
+        plan = make(*a, **kw)
+        plan.set_tile_order(request.param)
+        return plan
+
+    monkeypatch.setattr(binding, "shard_plan", planned)
+    return request.param

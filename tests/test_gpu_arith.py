@@ -224,7 +224,7 @@ def test_arith_every_pattern_pair():
         del old, dst, pos, w_esc, w_val
 
 
-def test_arith_few_workers_dense_changes():
+def test_arith_few_workers_dense_changes(tile_order):
     """Arithmetic payloads through the regime where tiles are counted first and walked again (two
     tickets of one group in a row) and where tiles are too dense to park, with and without refresh."""
     ts = models.decoder(2, 1024, 16, 16, 64, 2816, 4096, fused=True)

@@ -161,7 +161,7 @@ def run_and_check(tensors, tp, recipe, seed, sample, density=None, cap_frac=None
     return totals
 
 
-def test_decoder7b_tp4_p05():
+def test_decoder7b_tp4_p05(tile_order):
     """7B-style decoder, TP=4, Bernoulli(0.05): the workload bench.py times."""
     print("case: decoder7b tp=4 p=0.05 seed=0", flush=True)
     ts = models.decoder_7b()
@@ -183,7 +183,7 @@ def test_decoder7b_tp4_p05_arithmetic_payload():
 
 
 @pytest.mark.parametrize("p", [0.001, 0.01, 0.1, 0.5])
-def test_flat_2pow30_density_sweep(p):
+def test_flat_2pow30_density_sweep(p, tile_order):
     """One flat 2^30-element tensor, TP=1, int32 indices up to 2^30 - 1."""
     print("case: flat 2^30 p=%g seed=0" % p, flush=True)
     # the oracle on the whole tensor at the low densities, on a window of 2^24 elements that starts in

@@ -36,7 +36,7 @@ def test_config1_single_matrix():
 
 @pytest.mark.parametrize("tp", [1, 2, 4, 8])
 @pytest.mark.parametrize("fused", [True, False])
-def test_small_decoder_all_rules(tp, fused):
+def test_small_decoder_all_rules(tp, fused, tile_order):
     print("case: small decoder tp=%d fused=%s" % (tp, fused), flush=True)
     ts = models.decoder(2, 320, 8, 8 if not fused else 8, 40, 1376, 2048, fused=fused)
     full_parity(bern_case(ts, tp, 0.05, seed=11 + tp))
@@ -49,14 +49,14 @@ def test_gqa_decoder_tp8_one_kv_head_per_shard():
 
 
 @pytest.mark.parametrize("p", [0.0, 0.001, 0.5, 1.0])
-def test_densities(p):
+def test_densities(p, tile_order):
     print("case: densities p=%g" % p, flush=True)
     ts = [T(96, 1024, R.SPLIT_ROWS), T(64, 2048, R.SPLIT_COLS), T(1, 5000, R.REPLICATED)]
     full_parity(bern_case(ts, 4, p, seed=21))
 
 
 @pytest.mark.parametrize("numel", [1, 7, 8, 9, 63, 511, 513, TILE - 1, TILE, TILE + 1, 3 * TILE + 17])
-def test_ragged_flat_sizes(numel):
+def test_ragged_flat_sizes(numel, tile_order):
     print("case: ragged flat numel=%d" % numel, flush=True)
     full_parity(bern_case([T(1, numel, R.REPLICATED)], 2, 0.3, seed=numel))
 
@@ -135,7 +135,7 @@ def test_fp32_rounding_special_values():
     assert np.array_equal(want[0]["val"], rb[rb != 0])
 
 
-def test_few_workers_dense_changes():
+def test_few_workers_dense_changes(tile_order):
     """Few workers and tiles that fill the LDS ring: workers wait often and take tickets at a low
     rate, so one worker gets two tickets of one group of blocks in a row; the kernel then
     publishes that pair's counts before it may wait again.  The result must not depend on any of
@@ -154,7 +154,7 @@ def test_few_workers_dense_changes():
 
 
 @pytest.mark.parametrize("p", [0.45, 0.8, 1.0])
-def test_dense_tiles_are_counted_ahead(p):
+def test_dense_tiles_are_counted_ahead(p, tile_order):
     """More than a third of the elements change: the ring does not hold a ticket's three tiles, and a
     workgroup counts the rest of its ticket before it waits for room (word 3 of the workspace header
     counts how often).  Same buckets as ever."""
@@ -271,6 +271,22 @@ def test_bandwidth_probes_move_what_they_say():
         for j in range(4):
             want ^= av[c * 1024 + j * 256] ^ bv[c * 1024 + j * 256]
         assert np.array_equal(dst[c * per_chunk:c * per_chunk + 16].cpu().numpy(), want), c
+    # the line probe changes whole 64-byte lines, about the stated share of them, first word of each
+    # 16-byte part incremented, everything else as it was
+    buf = torch.zeros(1 << 22, dtype=torch.int32, device="cuda")            # 16 MiB = 262,144 lines
+    R.bw_probe_lines(buf, 0.3)
+    torch.cuda.synchronize()
+    parts = buf.view(-1, 4).cpu().numpy()
+    assert (parts[:, 1:] == 0).all() and set(np.unique(parts[:, 0])) <= {0, 1}
+    lines = parts[:, 0].reshape(-1, 4)
+    assert ((lines.sum(1) == 0) | (lines.sum(1) == 4)).all()
+    n = lines.shape[0]
+    assert abs(int((lines.sum(1) == 4).sum()) - 0.3 * n) < 6 * (n * 0.3 * 0.7) ** 0.5
+    R.bw_probe_lines(buf, 1.0)
+    torch.cuda.synchronize()
+    assert int(buf.view(-1, 4)[:, 0].min()) >= 1
+    with pytest.raises(R.RoseError):
+        R.bw_probe_lines(buf[:24], 0.5)                  # not a multiple of 64 bytes
     with pytest.raises(R.RoseError):
         R.bw_probe_mixed(a[:1000], b[:1000], dst, per_chunk, sink)
     with pytest.raises(R.RoseError):

@@ -74,7 +74,7 @@ def receiver_shards(ts, recs, plan, tp, which, dummy):
 
 
 @pytest.mark.parametrize("tp_src,pp_src,tp,pp_dst", [(2, 2, 4, 1), (1, 1, 2, 2), (2, 4, 2, 2), (4, 1, 1, 4)])
-def test_pipeline_senders_feed_receivers_with_another_stage_split(tp_src, pp_src, tp, pp_dst):
+def test_pipeline_senders_feed_receivers_with_another_stage_split(tp_src, pp_src, tp, pp_dst, tile_order):
     print("case: pipeline tp_src=%d pp_src=%d -> tp=%d pp_dst=%d" % (tp_src, pp_src, tp, pp_dst), flush=True)
     n_layers = 4
     ts, recs = model(n_layers, seed=40 + pp_src, p=0.08)

@@ -34,7 +34,7 @@ def random_tensors(rng, tp):
 
 
 @pytest.mark.parametrize("seed", range(40))
-def test_random_parameter_sets(seed):
+def test_random_parameter_sets(seed, tile_order):
     rng = np.random.default_rng(1000 + seed)
     tp = int(rng.choice([1, 2, 3, 4, 8]))
     p = [0.003, 0.05, 0.3, 1.0, 0.0][seed % 5]
@@ -47,7 +47,7 @@ def test_random_parameter_sets(seed):
 
 
 @pytest.mark.parametrize("seed", [278] + list(range(24)))
-def test_random_parameter_sets_from_sharded_senders(seed):
+def test_random_parameter_sets_from_sharded_senders(seed, tile_order):
     """The same kind of random sets, sent by every sender of a random degree to a random destination
     degree (seed 278: one column per sender and row, found by a longer run of this sweep)."""
     import math

@@ -34,7 +34,7 @@ def check_refresh(c):
 
 @pytest.mark.parametrize("tp", [1, 4])
 @pytest.mark.parametrize("p", [0.01, 0.3])
-def test_refresh_small_decoder(tp, p):
+def test_refresh_small_decoder(tp, p, tile_order):
     print("case: refresh small decoder tp=%d p=%g" % (tp, p), flush=True)
     ts = models.decoder(2, 320, 8, 8, 40, 1376, 2048, fused=True)
     check_refresh(bern_case(ts, tp, p, seed=50 + tp))
@@ -71,7 +71,7 @@ def test_refresh_fp32_master():
     check_refresh(Case(ts, 4, olds, news))
 
 
-def test_refresh_few_workers_dense():
+def test_refresh_few_workers_dense(tile_order):
     """The regime where tiles are walked twice (two tickets of one group in a row): a tile must
     not be refreshed before its second walk."""
     print("case: refresh few workers", flush=True)

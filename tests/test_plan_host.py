@@ -307,3 +307,12 @@ def test_pipeline_plan_argument_errors():
         assert e.value.status == status, kw
     # one stage on both sides ignores the layer field altogether
     R.shard_plan([dict(t, layer=99) for t in ts], 4)
+
+
+def test_tile_order_setter_checks_its_argument():
+    plan = R.shard_plan([dict(name="w", rows=8, cols=8, rule=R.SPLIT_ROWS, sections=None)], 2)
+    for order in (binding.TILE_ORDER_AUTO, binding.TILE_ORDER_SPREAD, binding.TILE_ORDER_NEIGHBOURS):
+        plan.set_tile_order(order)
+    for bad in (-1, 3):
+        with pytest.raises(R.RoseError):
+            plan.set_tile_order(bad)
