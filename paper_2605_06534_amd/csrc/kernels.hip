@@ -646,6 +646,12 @@ enum : int { kWalkTile = 0, kWalkNeedTicket = 1, kWalkDone = 2 };
 __device__ __forceinline__ void walk_accept(const EncodeArgs &a, Walk &w, uint32_t n) {
     if (n >= (uint32_t)a.n_tickets) {
         w.exhausted = true;
+    } else if ((int32_t)n <= w.ticket) {
+        // One counter hands the tickets out in order, so a worker's tickets increase.  A value that
+        // does not is not a ticket (the register it arrives in is only reserved by asking the
+        // compiler, see ticket_request): walk no further and mark the launch as failed.
+        __hip_atomic_store(a.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        w.exhausted = true;
     } else {
         w.next_ticket = (int32_t)n;
         w.have_next = true;
