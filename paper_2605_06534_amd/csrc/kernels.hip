@@ -492,6 +492,9 @@ static_assert((kRing & (kRing - 1)) == 0 && (kQueue & (kQueue - 1)) == 0 && kQue
 
 enum : int { kLoadVec = 0, kLoadGeneral = 1 };
 enum : int { kDrainOldest = 0, kDrainAll = 1, kDrainReady = 2 };
+#ifndef ROSE_ALIGN_STORES
+#define ROSE_ALIGN_STORES 1
+#endif
 
 
 struct TileCtx {
@@ -799,18 +802,17 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 l_shift = pc.shift;
                 l_stride = (uint32_t)pc.lstride;
             }
-#if ROSE_DIAG & 16
-            // timing experiment only (wrong buckets): every run starts and ends on a 128-byte boundary of
-            // the index stream (64 of the value stream), as if neighbouring runs never shared a line
-            const u64 excl_x = excl & ~(u64)31;
-            const uint32_t cnt_x = (cnt + 31u) & ~31u;
-#else
-            const u64 excl_x = excl;
-            const uint32_t cnt_x = cnt;
-#endif
-            for (uint32_t k = threadIdx.x; k < cnt_x; k += kThreads) {
-                const u64 pos = excl_x + k;
-                if (pos < (u64)b.capacity) {
+            // A wave's store covers 64 entries = 256 bytes of indices, 128 of values.  The run starts at an
+            // arbitrary entry of the bucket, so the threads are lined up with the BUCKET, not with the run:
+            // thread t of a round handles the entry whose position is t more than a multiple of 32
+            // entries.  Every store but the first and last of a run then fills whole 64-byte lines
+            // (otherwise each wave's store starts and ends inside a line and the line's 32-byte halves
+            // are written twice: 1.20 x the bytes at the memory).
+            const uint32_t phase = ROSE_ALIGN_STORES ? (uint32_t)excl & 31u : 0u;
+            for (uint32_t kk = threadIdx.x; kk < cnt + phase; kk += kThreads) {
+                const uint32_t k = kk - phase;         // (wraps below phase: caught by the first test)
+                const u64 pos = excl + k;
+                if (kk >= phase && pos < (u64)b.capacity) {
                     const uint32_t entry = s_ring[(off + k) & (kRing - 1)];
                     const uint32_t base = k < c1 ? b0 : k < c2 ? b1 : k < c3 ? b2 : b3;
                     uint32_t local = base + (ARITH ? (entry >> 16) & (uint32_t)(kTile - 1) : entry >> 16);
@@ -1580,7 +1582,7 @@ __device__ __forceinline__ void apply_body(const BucketDev &b, int32_t n_tensors
             // of the next round (the run's last chunk only looks into them)
             int32_t nxt_idx_raw = 0;
             uint32_t nxt_val = 0;
-            if (e2 < total) {
+            if (e2 < total && (lane < kLineElems || wbase + 64 < wend)) {     // whole only if the run goes on
 #if ROSE_APPLY_NT & 1
                 nxt_idx_raw = __builtin_nontemporal_load(b.idx + e2);
                 nxt_val = __builtin_nontemporal_load(b.val + e2);
