@@ -104,7 +104,18 @@ def profile_traffic(name, density, kernel):
             nbytes = 1024.0 * (float(kv["fetch_KiB"]) * float(kv["fetch_scale"]) +
                                float(kv["write_KiB"]) * float(kv["write_scale"]))
             return nbytes, src
-    return None, {"note": "no TRAFFIC line for this workload, density and kernel under profiles/"}
+    src = {"note": "no TRAFFIC line for this workload, density and kernel under profiles/"}
+    # counters taken on a part of the workload (same shapes, fewer layers) are named, never scaled up
+    for fn in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if fn.endswith("_hbm_traffic.txt"):
+            for line in open(os.path.join(pdir, fn)):
+                kv = dict(x.split("=", 1) for x in line.split()[1:] if "=" in x) if line.startswith("TRAFFIC ") else {}
+                if kv.get("kernel") == kernel and kv.get("workload", "").startswith(name + "_") and kv.get("density") == want["density"]:
+                    src["related"] = {"file": "profiles/" + fn, "workload": kv["workload"],
+                                      "bytes": round(1024.0 * (float(kv["fetch_KiB"]) * float(kv["fetch_scale"]) +
+                                                               float(kv["write_KiB"]) * float(kv["write_scale"]))),
+                                      "kernels_sha256_matches": kv.get("kernels_sha256") == kernels_sha256()}
+    return None, src
 
 
 def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_host_sample):
