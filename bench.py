@@ -254,6 +254,9 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
     local_elems = sum(plan.local_numel(t, d) for t in range(len(tensors)) for d in range(tp))
     dens = nnz_total / max(local_elems, 1)
     app_line_bytes = 6 * nnz_total + 2 * (1 - (1 - dens) ** 32) * 2 * local_elems
+    # what the memory moves for it (counters): reads come in 128-byte units (both halves of an L2 line
+    # are fetched when one is asked for), writes in the 64-byte lines the kernel stores
+    app_mem_bytes = 6 * nnz_total + ((1 - (1 - dens) ** 64) + (1 - (1 - dens) ** 32)) * 2 * local_elems
     res = {
         "name": name, "n_elems": n_elems, "n_tensors": len(tensors), "tp": tp, "recipe": recipe, "density": p,
         "nnz": nnz_total, "new_dtype": "fp32->bf16 RNE" if new_dtype == R.FP32_RNE else "bf16",
@@ -263,6 +266,8 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
         "enc_frac": enc_bytes / 1e9 / (t_enc / 1e3) / HBM_PEAK_GBS,
         "both_frac": (enc_bytes + app_bytes) / 1e9 / ((t_enc + t_app) / 1e3) / HBM_PEAK_GBS,
         "app_line_frac": app_line_bytes / 1e9 / (t_app / 1e3) / HBM_PEAK_GBS if t_app > 0 else None,
+        "app_mem_bytes": app_mem_bytes,
+        "app_mem_frac": app_mem_bytes / 1e9 / (t_app / 1e3) / HBM_PEAK_GBS if t_app > 0 else None,
     }
     if keep_host_sample:
         res["host_sample"] = host_sample(tensors, olds, news, args.cpu_sample_elems)
@@ -412,6 +417,8 @@ def main():
                    "encode_plus_apply_algorithmic_frac_of_peak": round(m["both_frac"], 4),
                    "apply_line_model_bytes": int(m["app_line_bytes"]),
                    "apply_line_model_frac_of_peak": round(m["app_line_frac"], 4) if m["app_line_frac"] else None,
+                   "apply_memory_model_bytes": int(m["app_mem_bytes"]),
+                   "apply_memory_model_frac_of_peak": round(m["app_mem_frac"], 4) if m["app_mem_frac"] else None,
                    "t_dense_copy_ms": round(m["t_copy"], 4),
                    "wire_bytes_sparse_over_dense": round(6 * m["nnz"] / (2 * m["n_elems"]), 4),
                    "modelled_sync": crossover,
@@ -430,7 +437,8 @@ def main():
                                  "value_GBs_scanned": round(e["scanned"] / 1e9 / (e["ms_per_step"] / 1e3), 1),
                                  "encode_frac_of_peak": round(e["enc_frac"], 4),
                                  "encode_plus_apply_algorithmic_frac_of_peak": round(e["both_frac"], 4),
-                                 "apply_line_model_frac_of_peak": round(e["app_line_frac"], 4)}
+                                 "apply_line_model_frac_of_peak": round(e["app_line_frac"], 4),
+                                 "apply_memory_model_frac_of_peak": round(e["app_mem_frac"], 4)}
         out["detail"]["decoder7b_tp4"] = extra
 
     if want_cpu:
