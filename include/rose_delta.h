@@ -228,7 +228,8 @@ rose_status rose_plan_n_tiles(const rose_plan *plan, int64_t *n_tiles);
  *                       (row-major; bf16, or fp32 for new when new_dtype = ROSE_FP32_RNE).
  *                       Tensors aligned to 16 bytes take the 128-bit load path; others still
  *                       work, more slowly.  Both are only read.
- *   buckets             HOST array of tp bucket structs; their device arrays are written.
+ *   buckets             HOST array of rose_plan_n_buckets bucket structs (tp of them; tp * pp_dst for a
+ *                       pipeline plan); their device arrays are written.
  *   workspace           DEVICE scratch of at least rose_plan_workspace_bytes, 256-byte aligned;
  *                       contents before the call do not matter; calls that share a workspace
  *                       must be ordered on one stream.
