@@ -128,3 +128,34 @@ def test_pipeline_object_for_a_bucket_the_receiver_does_not_have_is_turned_away(
     assert all(torch.equal(a, r) for a, r in zip(shards[1], ref))
     with pytest.raises(R.RoseError):
         R.object_check(small, obj)
+
+
+def test_pipeline_sender_refresh_touches_only_its_stage():
+    """Encode with sender refresh on a pipeline plan: the sender's own tensors (sent or only held, like
+    the replicated ones another rank sends) end equal to the new ones, the stand-in buffer behind the
+    other stages' table entries is never read or written, and the buckets are the oracle's."""
+    print("case: pipeline refresh tp_src=2 pp_src=2 -> tp=4 pp_dst=1", flush=True)
+    n_layers, tp, tp_src, pp_src, pp_dst = 4, 4, 2, 2, 1
+    ts, recs = model(n_layers, seed=52, p=0.1)
+    dummy = torch.zeros(64, dtype=torch.int16, device="cuda")
+    for st in range(pp_src):
+        for s in range(tp_src):
+            plan = R.shard_plan(ts, tp, tp_src, s, n_layers, pp_src, st, pp_dst)
+            held = [plan.stage_of(i)[0] == st for i in range(len(ts))]
+            sl = [dict(r, old=cut(r["old"], r, tp_src, s), new=cut(r["new"], r, tp_src, s)) for r in recs]
+            olds = [dev(x["old"]) if h else dummy for x, h in zip(sl, held)]
+            news = [dev(x["new"]) if h else dummy for x, h in zip(sl, held)]
+            buckets = [R.Bucket(plan.bucket_capacity(b), len(ts)) for b in range(plan.n_buckets)]
+            R.delta_encode_refresh(plan, R.ptr_table(olds), R.ptr_table(news), R.BF16, buckets, R.workspace(plan))
+            torch.cuda.synchronize()
+            want = oracle.encode_model_pp(sl, tp, tp_src, s, n_layers, pp_src, st, pp_dst)
+            for b in range(plan.n_buckets):
+                n = R.bucket_check(plan, buckets[b])
+                got = {"idx": buckets[b].idx[:n].cpu().numpy(), "val": buckets[b].val[:n].cpu().numpy().view(np.uint16),
+                       "seg_off": buckets[b].seg_off.cpu().numpy()}
+                assert_buckets_equal(got, want[b], "sender (tp %d, stage %d) bucket %d" % (s, st, b))
+            for i, h in enumerate(held):
+                if h:
+                    assert torch.equal(olds[i], news[i]), ("not refreshed", st, s, ts[i]["name"])
+                    assert plan.tensor_is_read(i, R.ENCODE_REFRESH)
+    assert torch.count_nonzero(dummy).item() == 0
