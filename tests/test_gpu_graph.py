@@ -15,8 +15,9 @@ from test_gpu_parity import bern_case
 pytestmark = pytest.mark.gpu
 
 
-def test_step_in_a_graph_replays_exactly():
-    print("case: graph capture of encode + apply", flush=True)
+@pytest.mark.parametrize("entry", ["workspace", "built_in_scratch"])
+def test_step_in_a_graph_replays_exactly(entry, tile_order):
+    print("case: graph capture of encode + apply, %s, tile order %d" % (entry, tile_order), flush=True)
     tp = 2
     ts = models.decoder(2, 320, 8, 8, 40, 1376, 2048, fused=True)
     c = bern_case(ts, tp, 0.05, seed=90)
@@ -28,11 +29,15 @@ def test_step_in_a_graph_replays_exactly():
     new_shards = [c.shard_init(d, [r["new"] for r in recs]) for d in range(tp)]
 
     def step():
-        R.delta_encode(c.plan, c.old_tab, c.new_tab, c.new_dtype, c.buckets, c.ws)
+        if entry == "workspace":
+            R.delta_encode(c.plan, c.old_tab, c.new_tab, c.new_dtype, c.buckets, c.ws)
+        else:                                # the entry point for callers that cannot allocate, e.g. under capture
+            R.delta_encode_static(c.plan, c.old_tab, c.new_tab, c.new_dtype, 0, c.buckets)
         for d in range(tp):
             R.delta_apply(c.plan, d, c.buckets[d], tabs[d])
 
-    step()                                   # eager once: uploads the plan's tables, warms everything
+    c.plan.upload()                          # the built-in-scratch entry never makes a plan resident by itself
+    step()                                   # eager once: warms everything
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
