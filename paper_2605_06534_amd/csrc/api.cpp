@@ -14,8 +14,17 @@ constexpr int32_t kNeighboursBelowPpm = 55000;   // see encode_common
 // Copy the piece and tile tables to the current device once; later calls on the same device
 // reuse them.  A plan is bound to the first device it is used on.  `may_allocate` = false: only
 // report whether the plan is resident here (nothing is allocated, ROSE_ERR_SCRATCH if it is not).
+rose_status device_tables_locked(const rose_plan *p, bool may_allocate);
 rose_status device_tables(const rose_plan *p, bool may_allocate = true) {
     std::lock_guard<std::mutex> lock(p->mu);
+    try {
+        return device_tables_locked(p, may_allocate);
+    } catch (...) {                                     // host memory ran out while building the tables
+        return ROSE_ERR_HIP;
+    }
+}
+
+rose_status device_tables_locked(const rose_plan *p, bool may_allocate) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return ROSE_ERR_HIP;
     if (p->device == dev) return ROSE_OK;
