@@ -181,7 +181,7 @@ rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
 /*
  * The order in which the encode kernel's workgroups take tiles (it changes speed only: the buckets
  * are the same bytes either way).  ROSE_TILE_ORDER_SPREAD: a workgroup takes tiles that lie 64 tiles
- * apart, so that the prefix sums across workgroups are ready soonest; best above about 6 % of changed
+ * apart, so that the prefix sums across workgroups are ready soonest; best above about 7.5 % of changed
  * elements.  ROSE_TILE_ORDER_NEIGHBOURS: it takes three neighbouring tiles and writes their entries
  * as one run, which shares fewer 64-byte lines of the bucket with other workgroups; best at low
  * densities.  ROSE_TILE_ORDER_AUTO_PICK (the default): the library picks, from the density of the

@@ -9,7 +9,7 @@ namespace {
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-constexpr int32_t kNeighboursBelowPpm = 55000;   // see encode_common
+constexpr int32_t kNeighboursBelowPpm = 75000;   // see encode_common
 
 // Copy the piece and tile tables to the current device once; later calls on the same device
 // reuse them.  A plan is bound to the first device it is used on.  `may_allocate` = false: only
@@ -168,8 +168,8 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     const bool f32 = new_dtype == ROSE_FP32_RNE;
     const int resident = p->resident[(f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0)];
     // Tile order: the caller's choice, else picked from the density the plan's last checked launch showed
-    // (7B-style workload, neighbours against spread: 3.2 / 1.3 / 0.8 % faster at 1 / 2 / 5 %, 7 / 15 % slower
-    // at 8 / 10 %).
+    // (7B-style workload, neighbours against spread on the same buffers: 2.7 / 1.8 / 1.4 / 1.0 % faster at
+    // 1 / 2 / 5 / 7 %, 2 / 13 % slower at 8 / 10 %).
     int order = p->tile_order.load(std::memory_order_relaxed);
     if (order == ROSE_TILE_ORDER_AUTO_PICK) {
         const int32_t ppm = p->seen_density_ppm.load(std::memory_order_relaxed);
