@@ -194,9 +194,9 @@ def test_flat_2pow30_density_sweep(p, tile_order):
     assert abs(totals[0] - p * n) < 6 * (n * p * (1 - p)) ** 0.5
 
 
-def test_decoder32b_tp8_p02():
+def test_decoder32b_tp8_p02(tile_order):
     """32B-style GQA decoder, TP=8 (one KV head per shard), Bernoulli(0.02); old + new are 131 GB resident."""
-    print("case: decoder32b tp=8 p=0.02 seed=0", flush=True)
+    print("case: decoder32b tp=8 p=0.02 seed=0 tile order %d" % tile_order, flush=True)
     free, _ = torch.cuda.mem_get_info()
     if free < 165e9:
         pytest.skip("needs about 160 GB of free device memory")
@@ -206,20 +206,20 @@ def test_decoder32b_tp8_p02():
 
 
 @pytest.mark.parametrize("tp", [1, 4])
-def test_decoder8b_shapes(tp):
+def test_decoder8b_shapes(tp, tile_order):
     """8B-style GQA decoder (the paper's smaller model), at the rollout side's TP=1 and the training
     side's TP=4; Bernoulli(0.02)."""
-    print("case: decoder8b tp=%d p=0.02 seed=1" % tp, flush=True)
+    print("case: decoder8b tp=%d p=0.02 seed=1 tile order %d" % (tp, tile_order), flush=True)
     ts = models.decoder_8b()
     sample = [0, 1, 2, 3, 5, 6, len(ts) - 2, len(ts) - 1]
     run_and_check(ts, tp, "bernoulli", 1, sample, density=0.02, p=0.02)
 
 
-def test_decoder32b_tp8_fp32_master_clustered():
+def test_decoder32b_tp8_fp32_master_clustered(tile_order):
     """fp32-master input with per-row Beta(0.5, 20) change rates on the whole 32B-style set: old
     (65.5 GB) and the fp32 new weights (131 GB) are resident, the receiver's shards are built and
     checked one shard at a time."""
-    print("case: decoder32b tp=8 clustered fp32 seed=0", flush=True)
+    print("case: decoder32b tp=8 clustered fp32 seed=0 tile order %d" % tile_order, flush=True)
     free, _ = torch.cuda.mem_get_info()
     if free < 245e9:
         pytest.skip("needs about 240 GB of free device memory, %.0f GB are free" % (free / 1e9))
