@@ -73,10 +73,10 @@ def receiver_shards(ts, recs, plan, tp, which, dummy):
     return out
 
 
-@pytest.mark.parametrize("tp_src,pp_src,tp,pp_dst", [(2, 2, 4, 1), (1, 1, 2, 2), (2, 4, 2, 2), (4, 1, 1, 4)])
-def test_pipeline_senders_feed_receivers_with_another_stage_split(tp_src, pp_src, tp, pp_dst, tile_order):
-    print("case: pipeline tp_src=%d pp_src=%d -> tp=%d pp_dst=%d" % (tp_src, pp_src, tp, pp_dst), flush=True)
-    n_layers = 4
+@pytest.mark.parametrize("n_layers,tp_src,pp_src,tp,pp_dst",
+                         [(4, 2, 2, 4, 1), (4, 1, 1, 2, 2), (4, 2, 4, 2, 2), (4, 4, 1, 1, 4), (6, 1, 3, 2, 2), (6, 2, 2, 2, 3)])
+def test_pipeline_senders_feed_receivers_with_another_stage_split(n_layers, tp_src, pp_src, tp, pp_dst, tile_order):
+    print("case: pipeline %d layers tp_src=%d pp_src=%d -> tp=%d pp_dst=%d" % (n_layers, tp_src, pp_src, tp, pp_dst), flush=True)
     ts, recs = model(n_layers, seed=40 + pp_src, p=0.08)
     dummy = torch.zeros(64, dtype=torch.int16, device="cuda")
     # the receivers know nothing of the senders' split: their plan is made with one sending stage

@@ -246,13 +246,14 @@ def test_which_pointer_table_entries_a_launch_reads():
         R.shard_plan(ts, 4).tensor_is_read(5)
 
 
-@pytest.mark.parametrize("pp_src,pp_dst,tp_src,tp", [(2, 1, 2, 4), (1, 2, 1, 2), (4, 2, 2, 1), (2, 4, 1, 4), (2, 2, 4, 2)])
-def test_pipeline_plan_matches_oracle_stages_and_maps(pp_src, pp_dst, tp_src, tp):
+@pytest.mark.parametrize("n_layers,pp_src,pp_dst,tp_src,tp",
+                         [(4, 2, 1, 2, 4), (4, 1, 2, 1, 2), (4, 4, 2, 2, 1), (4, 2, 4, 1, 4), (4, 2, 2, 4, 2),
+                          (6, 3, 2, 1, 2), (6, 6, 3, 2, 2), (6, 3, 1, 2, 1), (6, 2, 6, 4, 2)])
+def test_pipeline_plan_matches_oracle_stages_and_maps(n_layers, pp_src, pp_dst, tp_src, tp):
     """The plan of a sender (tensor-parallel rank s in pipeline stage st) lists the whole model: its
     tables must hold, for every element of every tensor of the sender's stage, the oracle's
     destination under the receiving side's degree, in the bucket of the oracle's receiving stage,
     and nothing for the tensors of other stages."""
-    n_layers = 4
     ts = models.decoder(n_layers, 32, 4, 4, 8, 48, 64, fused=True)
     for st in range(pp_src):
         for s in range(tp_src):
