@@ -36,9 +36,14 @@ def parse():
     ap.add_argument("--density", type=float, default=None, help="change density p (default: the workload's)")
     ap.add_argument("--layers", type=int, default=None, help="fewer decoder layers (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--tp", type=int, default=None, help="receiving side's tensor-parallel degree (default: the workload's)")
     ap.add_argument("--tp-src", type=int, default=1,
                     help="sender-side sharding: time the sender that holds shard --src-rank of this many")
     ap.add_argument("--src-rank", type=int, default=0)
+    ap.add_argument("--pp-src", type=int, default=1, help="pipeline stages on the sending side (the step is "
+                    "then one sender's share: the tensors of --stage-src)")
+    ap.add_argument("--stage-src", type=int, default=0)
+    ap.add_argument("--pp-dst", type=int, default=1, help="pipeline stages on the receiving side (tp * pp-dst buckets)")
     ap.add_argument("--payload", choices=("new", "arith"), default="new",
                     help="entry payload: the new pattern (default) or the arithmetic difference with escapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -124,37 +129,56 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
     dev = torch.device("cuda:0")
     n_elems = models.numel(tensors)
 
+    # ---- the plan: this sender's view of the whole model (host only so far) ----
+    staged = args.pp_src > 1 or args.pp_dst > 1
+    if staged:
+        n_layers = max(t["layer"] for t in tensors) + 1
+        plan = R.shard_plan(tensors, tp, args.tp_src, args.src_rank, n_layers, args.pp_src, args.stage_src, args.pp_dst)
+    else:
+        plan = R.shard_plan(tensors, tp, args.tp_src, args.src_rank)
+    n_b = plan.n_buckets                                    # tp, or tp * pp_dst
+    held = [plan.stage_of(t)[0] == args.stage_src for t in range(len(tensors))]
+
     # ---- inputs resident in HBM: W_{t-1}, W_t, the receiver's shard copies, buckets ----
+    # (a tensor of another sending stage is not on this sender: its table entries are never read and
+    # point at a few valid bytes)
+    stand_in = torch.zeros(64, dtype=torch.bfloat16, device=dev)
     olds, news = [], []
     kw = {"p": p} if recipe == "bernoulli" else {"vocab_active": 20000}
-    for _, _, o, n in synth.model_pairs(tensors, recipe, args.seed, "cuda", **kw):
-        olds.append(o)
-        news.append(n)
+    for _, _, o, n in synth.model_pairs(tensors, recipe, args.seed, "cuda", only=held, **kw):
+        olds.append(stand_in if o is None else o)
+        news.append(stand_in if n is None else n)
     new_dtype = R.FP32_RNE if recipe == "clustered_f32" else R.BF16
+    if staged and new_dtype != R.BF16:
+        print("bench.py: --pp-src / --pp-dst are for bf16 workloads", file=sys.stderr)
+        sys.exit(2)
     if args.tp_src > 1:
         # the sender's slices of W_{t-1} and W_t, cut with the library's own dense path
         if new_dtype != R.BF16:
             print("bench.py: --tp-src is for bf16 workloads", file=sys.stderr)
             sys.exit(2)
-        cut = R.shard_plan(tensors, args.tp_src)
-        full_old, full_new = R.ptr_table(olds), R.ptr_table(news)
-        so = [torch.empty(cut.local_numel(t, args.src_rank), dtype=torch.bfloat16, device=dev) for t in range(len(tensors))]
+        mine = [t for t in range(len(tensors)) if held[t]]
+        cut = R.shard_plan([tensors[t] for t in mine], args.tp_src)
+        full_old, full_new = R.ptr_table([olds[t] for t in mine]), R.ptr_table([news[t] for t in mine])
+        so = [torch.empty(cut.local_numel(k, args.src_rank), dtype=torch.bfloat16, device=dev) for k in range(len(mine))]
         sn = [torch.empty_like(x) for x in so]
         R.dense_copy(cut, args.src_rank, full_old, R.BF16, R.ptr_table(so))
         R.dense_copy(cut, args.src_rank, full_new, R.BF16, R.ptr_table(sn))
         torch.cuda.synchronize()
-        olds, news = so, sn
-        del cut, full_old, full_new
+        for k, t in enumerate(mine):
+            olds[t], news[t] = so[k], sn[k]
+        del cut, full_old, full_new, so, sn
         torch.cuda.empty_cache()
-        n_elems = sum(x.numel() for x in olds)
-    plan = R.shard_plan(tensors, tp, args.tp_src, args.src_rank)
+    if staged or args.tp_src > 1:
+        n_elems = sum(olds[t].numel() for t in range(len(tensors)) if held[t])
     old_tab, new_tab = R.ptr_table(olds), R.ptr_table(news)
     ws = R.workspace(plan)
     frac = 0.03 if p is None else min(1.0, 1.3 * p + 0.002)    # the clustered recipe changes about 1.6 %
-    buckets = [R.Bucket(int(plan.bucket_capacity(d) * frac) + 4096, len(tensors)) for d in range(tp)]
+    buckets = [R.Bucket(int(plan.bucket_capacity(d) * frac) + 4096, len(tensors)) for d in range(n_b)]
     shards, shard_tabs = [], []
-    for d in range(tp):
-        loc = [torch.zeros(plan.local_numel(t, d), dtype=torch.bfloat16, device=dev) for t in range(len(tensors))]
+    for d in range(n_b):
+        loc = [torch.zeros(plan.local_numel(t, d), dtype=torch.bfloat16, device=dev) if plan.local_numel(t, d) else stand_in
+               for t in range(len(tensors))]
         tab = R.ptr_table(loc)
         R.dense_copy(plan, d, old_tab, R.BF16, tab)        # receiver starts from W_{t-1} (the part this sender covers)
         shards.append(loc)
@@ -172,7 +196,7 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
             R.delta_encode(plan, old_tab, new_tab, new_dtype, buckets, ws)
         if ev:
             ev[1].record()
-        for d in range(tp):
+        for d in range(n_b):
             if arith:
                 R.delta_apply_ex(plan, d, buckets[d], R.PAYLOAD_ARITH, shard_tabs[d])
             else:
@@ -183,25 +207,26 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
     for _ in range(max(warmup, 1)):
         step()
     torch.cuda.synchronize()
-    nnz = [R.bucket_check(plan, buckets[d]) for d in range(tp)]    # raises if a bucket overflowed
+    nnz = [R.bucket_check(plan, buckets[d]) for d in range(n_b)]   # raises if a bucket overflowed
     nnz_total = sum(nnz)
 
     if arith:
         # an arithmetic bucket may be applied once only: start the receivers from W_{t-1} again and
         # take one step before checking (the timed steps below keep adding; their values are not used)
-        for d in range(tp):
+        for d in range(n_b):
             R.dense_copy(plan, d, old_tab, R.BF16, shard_tabs[d])
         step()
         torch.cuda.synchronize()
     # the receiver now holds W_t: check one shard tensor per rule class against a dense copy
     # (one tensor at a time: the largest workload leaves no room for a second copy of a whole shard)
     for t in range(len(tensors)):
-        if t % 7 == 0 or t >= len(tensors) - 3:            # walks through every rule class; both ends of the model
-            chk = shards[tp - 1][t].clone()
+        if held[t] and (t % 7 == 0 or t >= len(tensors) - 3):   # walks through every rule class; both ends of the model
+            last = plan.stage_of(t)[1] * tp + tp - 1           # the last shard of the stage that receives the tensor
+            chk = shards[last][t].clone()
             only = R.shard_plan([tensors[t]], tp, args.tp_src, args.src_rank)
             R.dense_copy(only, tp - 1, R.ptr_table([news[t]]), new_dtype, R.ptr_table([chk]))
             torch.cuda.synchronize()
-            if not torch.equal(shards[tp - 1][t].view(torch.int16), chk.view(torch.int16)):
+            if not torch.equal(shards[last][t].view(torch.int16), chk.view(torch.int16)):
                 print("bench.py: applied shard differs from the dense copy of the new weights (tensor %d)" % t,
                       file=sys.stderr)
                 sys.exit(1)
@@ -240,7 +265,7 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
     for rep in range(3):
         if rep == 1:
             ev_c[0].record()
-        for d in range(tp):
+        for d in range(n_b):
             R.dense_copy(plan, d, new_tab, new_dtype, shard_tabs[d])
     ev_c[1].record()
     torch.cuda.synchronize()
@@ -251,7 +276,7 @@ def measure(R, name, tensors, tp, recipe, p, args, steps, warmup, probes, keep_h
     enc_bytes = scanned + 6 * nnz_total            # algorithmic: read old + new once, write idx + val
     app_bytes = 8 * nnz_total                      # read idx + val, write val
     # apply moves whole 64-byte lines: entries read + touched lines read and written
-    local_elems = sum(plan.local_numel(t, d) for t in range(len(tensors)) for d in range(tp))
+    local_elems = sum(plan.local_numel(t, d) for t in range(len(tensors)) for d in range(n_b))
     dens = nnz_total / max(local_elems, 1)
     app_line_bytes = 6 * nnz_total + 2 * (1 - (1 - dens) ** 32) * 2 * local_elems
     # what the memory moves for it (counters): reads come in 128-byte units (both halves of an L2 line
@@ -376,7 +401,9 @@ def main():
     tensors, tp, recipe, p = workload(args.workload, args.layers)
     if args.density is not None:
         p = args.density
-    want_cpu = not args.no_cpu_baseline and args.tp_src == 1
+    if args.tp is not None:
+        tp = args.tp
+    want_cpu = not args.no_cpu_baseline and args.tp_src == 1 and args.pp_src == 1 and args.pp_dst == 1
     m = measure(R, args.workload, tensors, tp, recipe, p, args, args.steps, args.warmup, not args.no_probes, want_cpu)
 
     # Modelled synchronisation time over a link of B Gbit/s (the paper's range): the sparse path sends
@@ -391,7 +418,8 @@ def main():
     traffic, traffic_src = None, {"note": "non-default run: no committed profile applies"}
     if args.traffic_bytes is not None:
         traffic, traffic_src = args.traffic_bytes, {"note": "--traffic-bytes"}
-    elif args.layers is None and args.tp_src == 1 and args.seed == 0:
+    elif args.layers is None and args.tp_src == 1 and args.seed == 0 and args.tp is None \
+            and args.pp_src == 1 and args.pp_dst == 1:
         traffic, traffic_src = profile_traffic(args.workload, p, kernel.replace(" ", ""))
     value = m["scanned"] / 1e9 / (m["ms_per_step"] / 1e3)
     out = {
@@ -404,7 +432,8 @@ def main():
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": args.workload, "elements": m["n_elems"], "tensors": m["n_tensors"], "tp": tp,
                    "recipe": recipe, "density": p, "nnz": m["nnz"], "seed": args.seed,
-                   "tp_src": args.tp_src, "src_rank": args.src_rank, "hip_graph": bool(args.graph),
+                   "tp_src": args.tp_src, "src_rank": args.src_rank, "pp_src": args.pp_src,
+                   "stage_src": args.stage_src, "pp_dst": args.pp_dst, "hip_graph": bool(args.graph),
                    "payload": args.payload, "new_dtype": m["new_dtype"]},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": round(m["enc_bytes"] / 1e9 / (m["t_enc"] / 1e3), 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -426,7 +455,8 @@ def main():
     }
 
     # the other target configuration, in the same process: 7B-style decoder, TP = 4, at 1 / 5 / 10 %
-    if args.workload == "decoder32b_tp8" and not args.no_extra and args.layers is None and args.tp_src == 1:
+    if args.workload == "decoder32b_tp8" and not args.no_extra and args.layers is None and args.tp_src == 1 \
+            and args.pp_src == 1 and args.pp_dst == 1:
         extra = {}
         t7, tp7, rec7, _ = workload("decoder7b_tp4")
         for p7 in (0.01, 0.05, 0.1):

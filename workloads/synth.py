@@ -117,12 +117,17 @@ def pair_clustered_f32(rows, cols, seed, device="cpu", active_rows=None, sigma=1
     return old, new
 
 
-def model_pairs(tensors, recipe, seed, device="cpu", **kw):
+def model_pairs(tensors, recipe, seed, device="cpu", only=None, **kw):
     """Yield (ordinal, descriptor, old, new) for every tensor of a parameter set.
 
     recipe "bernoulli": kw p=...;  recipe "clustered_f32": kw vocab_active=... rows of the
-    vocabulary-split tensors (named embed / lm_head) that may change."""
+    vocabulary-split tensors (named embed / lm_head) that may change.  `only`: one flag per
+    tensor; a tensor whose flag is false is not generated (old = new = None), the others get the
+    values they would have had anyway."""
     for i, t in enumerate(tensors):
+        if only is not None and not only[i]:
+            yield i, t, None, None
+            continue
         s = tensor_seed(seed, i)
         if recipe == "bernoulli":
             old, new = pair_bernoulli(t["rows"] * t["cols"], kw["p"], s, device)
