@@ -184,13 +184,17 @@ rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
  * apart, so that the prefix sums across workgroups are ready soonest; best above about 7.5 % of changed
  * elements.  ROSE_TILE_ORDER_NEIGHBOURS: it takes three neighbouring tiles and writes their entries
  * as one run, which shares fewer 64-byte lines of the bucket with other workgroups; best at low
- * densities.  ROSE_TILE_ORDER_AUTO_PICK (the default): the library picks, from the density of the
+ * densities.  ROSE_TILE_ORDER_TIMED: four neighbouring tiles, and the entries are held in the
+ * workgroup until a window of time that all workgroups share (they read one clock), so that the
+ * memory sees the bucket writes in bursts instead of a steady trickle among the reads; best below
+ * about 4 %.  ROSE_TILE_ORDER_AUTO_PICK (the default): the library picks, from the density of the
  * plan's previous launch as far as rose_bucket_check has read it back (spread until then).
  * May be called at any time from any thread; a launch uses the value it finds.
  */
 #define ROSE_TILE_ORDER_AUTO_PICK 0
 #define ROSE_TILE_ORDER_SPREAD 1
 #define ROSE_TILE_ORDER_NEIGHBOURS 2
+#define ROSE_TILE_ORDER_TIMED 3
 rose_status rose_plan_set_tile_order(rose_plan *plan, int32_t order);
 
 /* Host queries on a plan (no GPU needed). */

@@ -16,7 +16,7 @@ REPLICATED, SPLIT_ROWS, SPLIT_COLS, FUSED_ROWS = 0, 1, 2, 3
 BF16, FP32_RNE = 0, 1
 OK, ERR_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_ALIGN, ERR_HIP, ERR_UNSUPPORTED, ERR_SCRATCH = range(8)
 LAYER_FIRST, LAYER_LAST = -1, -2
-TILE_ORDER_AUTO, TILE_ORDER_SPREAD, TILE_ORDER_NEIGHBOURS = 0, 1, 2
+TILE_ORDER_AUTO, TILE_ORDER_SPREAD, TILE_ORDER_NEIGHBOURS, TILE_ORDER_TIMED = 0, 1, 2, 3
 STATIC_SCRATCH_BYTES = 48 << 20
 
 _LIB_PATH = os.environ.get("ROSE_DELTA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)),

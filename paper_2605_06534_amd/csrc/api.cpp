@@ -9,7 +9,7 @@ namespace {
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-constexpr int32_t kNeighboursBelowPpm = 75000;   // see encode_common
+constexpr int32_t kNeighboursBelowPpm = 75000, kTimedBelowPpm = 40000;   // see encode_common
 
 // Copy the piece and tile tables to the current device once; later calls on the same device
 // reuse them.  A plan is bound to the first device it is used on.  `may_allocate` = false: only
@@ -169,15 +169,17 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     const int resident = p->resident[(f32 ? 1 : 0) + (refresh ? 2 : 0) + (arith ? 4 : 0)];
     // Tile order: the caller's choice, else picked from the density the plan's last checked launch showed
     // (7B-style workload, neighbours against spread on the same buffers: 2.7 / 1.8 / 1.4 / 1.0 % faster at
-    // 1 / 2 / 5 / 7 %, 2 / 13 % slower at 8 / 10 %).
+    // 1 / 2 / 5 / 7 %, 2 / 13 % slower at 8 / 10 %; timed against neighbours: 1.6 / 5 / 8 / 7 / 1 % faster at
+    // 0.5 / 1 / 2 / 3 / 4 %, 2 % slower at 5 %).
     int order = p->tile_order.load(std::memory_order_relaxed);
     if (order == ROSE_TILE_ORDER_AUTO_PICK) {
         const int32_t ppm = p->seen_density_ppm.load(std::memory_order_relaxed);
-        order = (ppm >= 0 && ppm < kNeighboursBelowPpm) ? ROSE_TILE_ORDER_NEIGHBOURS : ROSE_TILE_ORDER_SPREAD;
+        order = ppm < 0 ? ROSE_TILE_ORDER_SPREAD
+                        : ppm < kTimedBelowPpm ? ROSE_TILE_ORDER_TIMED
+                                               : ppm < kNeighboursBelowPpm ? ROSE_TILE_ORDER_NEIGHBOURS : ROSE_TILE_ORDER_SPREAD;
     }
     return rose::launch_encode(a, f32, refresh ? &r : nullptr, arith ? 1 : 0, resident,
-                               p->worker_cap.load(std::memory_order_relaxed), order == ROSE_TILE_ORDER_NEIGHBOURS,
-                               stream) == 0
+                               p->worker_cap.load(std::memory_order_relaxed), order, stream) == 0
                ? ROSE_OK
                : ROSE_ERR_HIP;
 }

@@ -309,6 +309,12 @@ constexpr u64 kValueMask = (1ull << kStatusShift) - 1;
 #define ROSE_DIAG 0           // timing experiments only: 1 no waiting for prefixes, 2 no bucket writes,
                               // 4 no publishing, 8 no parking in LDS
 #endif
+#ifndef ROSE_WRITE_PERIOD_LOG2
+#define ROSE_WRITE_PERIOD_LOG2 12     // ticks of the 100 MHz clock between windows (2^12: 41 us)
+#endif
+#ifndef ROSE_WRITE_OPEN_LOG2
+#define ROSE_WRITE_OPEN_LOG2 10       // ticks a window is open (2^10: 10 us)
+#endif
 #ifndef ROSE_COUNT_AHEAD
 #define ROSE_COUNT_AHEAD 1    // count the rest of a ticket's tiles before waiting for room (dense inputs)
 #endif
@@ -483,7 +489,8 @@ __device__ __forceinline__ void serve_blocks(const EncodeArgs &a, int32_t server
 #define ROSE_RING 8192
 #endif
 #ifndef ROSE_QUEUE
-#define ROSE_QUEUE 32         // (16 to 64 measure the same; the neighbours order parks about twice as many tiles)
+#define ROSE_QUEUE 64         // (16 to 64 measure the same in the spread order; the timed order holds tiles back for a
+                              // whole period between windows)
 #endif
 constexpr int kRing = ROSE_RING;        // entries parked per workgroup (power of two)
 constexpr int kQueue = ROSE_QUEUE;      // tiles parked per workgroup (<= 64)
@@ -589,7 +596,8 @@ __device__ __forceinline__ void load_raw_pair(const TileCtx &c, uint32_t t_off, 
     }
 }
 
-// The j-th tile of a ticket, or -1 if there is none.  A group of kBatch consecutive blocks has
+// The j-th tile of a ticket, or -1 if there is none.  A ticket stands for a.batch tiles (kBatch below; the
+// launcher picks it).  A group of kBatch consecutive blocks has
 // kBatch * kBlock tile positions ("slots", block after block) and kBlock tickets.  Two orders:
 // spread (a.adjacent = 0): ticket n of the group stands for position n of each of the group's blocks, so
 // that a block's 64 tiles are walked by 64 workers at once and its prefixes are ready one tile-time
@@ -605,10 +613,10 @@ __device__ __forceinline__ void load_raw_pair(const TileCtx &c, uint32_t t_off, 
 __device__ __forceinline__ int32_t ticket_tile(const EncodeArgs &a, int32_t ticket, int32_t j) {
     ticket = __builtin_amdgcn_readfirstlane(ticket);    // uniform anyway: keeps the table look-ups scalar
     j = __builtin_amdgcn_readfirstlane(j);
-    int32_t blk = (ticket / kBlock) * kBatch + j, pos = ticket & (kBlock - 1);
+    int32_t blk = (ticket / kBlock) * a.batch + j, pos = ticket & (kBlock - 1);
     if (a.adjacent) {
-        const int32_t slot = (ticket & (kBlock - 1)) * kBatch + j;
-        blk = (ticket / kBlock) * kBatch + slot / kBlock;
+        const int32_t slot = (ticket & (kBlock - 1)) * a.batch + j;
+        blk = (ticket / kBlock) * a.batch + slot / kBlock;
         pos = slot & (kBlock - 1);
     }
     if (blk >= a.n_blocks) return -1;
@@ -666,7 +674,7 @@ __device__ __forceinline__ void walk_accept(const EncodeArgs &a, Walk &w, uint32
 // is at hand (ask the counter, then call again); kWalkDone: no tiles are left.
 __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *tile) {
     for (;;) {
-        while (w.j + 1 < kBatch) {
+        while (w.j + 1 < a.batch) {
             ++w.j;
             const int32_t t = ticket_tile(a, w.ticket, w.j);
             if (t >= 0) {
@@ -674,7 +682,7 @@ __device__ __forceinline__ int walk_step(const EncodeArgs &a, Walk &w, int32_t *
                 return kWalkTile;
             }
         }
-        w.j = kBatch;
+        w.j = a.batch;
         if (w.redo && w.ticket == w.redo_through) w.redo = false;
         if (!w.have_next) return w.exhausted ? kWalkDone : kWalkNeedTicket;
         w.ticket = w.next_ticket;
@@ -892,7 +900,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
     // barrier of the following iteration.
     Walk walk;
     walk.ticket = -1;
-    walk.j = kBatch;
+    walk.j = a.batch;
     walk.next_ticket = 0;
     walk.redo_through = 0;
     walk.have_next = false;
@@ -1108,7 +1116,20 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
         }
         if (wave == 0) {
             const u64 unknown = __ballot(lane < q_len && !has_prefix(wq_w));
-            const int n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
+            int n_ready = unknown ? __ffsll((long long)unknown) - 1 : q_len;
+            // Timed order: bucket stores go out in windows of time that all workgroups share (a
+            // constant-rate clock every wave can read): a steady trickle of writes among the reads
+            // costs the memory far more than the same bytes written in bursts (a plain streaming
+            // kernel that reads two streams at 7.1 TB/s loses 22 % when it writes 1.5 % of what it
+            // reads tile by tile, and 6 % when it writes the same bytes in such windows).  Outside a
+            // window parked tiles simply stay parked, unless the ring or the queue is more than three
+            // quarters full.
+            if (a.timed) {
+                const uint32_t now = (uint32_t)__builtin_amdgcn_s_memrealtime();
+                const bool open = (now & ((1u << ROSE_WRITE_PERIOD_LOG2) - 1u)) < (1u << ROSE_WRITE_OPEN_LOG2);
+                const bool pressure = q_len > kQueue * 3 / 4 || ring_used > (uint32_t)kRing * 3 / 4;
+                if (!open && !pressure) n_ready = 0;
+            }
             if (lane < n_ready) s_excl[parity][lane] = wq_w & kValueMask;
             if (lane == 0) s_nready[parity] = n_ready;
             // ---- (c) poll: one lane per parked tile that has no prefix yet ----
@@ -1193,7 +1214,7 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 if (q_len > 0) drain(kDrainReady);
                 dense = q_len == kQueue || ring_used + tile_total > (uint32_t)kRing;
             }
-        } else if (__builtin_expect(ring_used + tile_total > (uint32_t)kRing && q_len < kBatch, 0)) {
+        } else if (__builtin_expect(ring_used + tile_total > (uint32_t)kRing && q_len < a.batch, 0)) {
             dense = mid_ticket;
         }
 #endif
@@ -1354,17 +1375,17 @@ __device__ __forceinline__ void encode_body(const EncodeArgs &a) {
                 // and tA is walked again from this iteration's tile on.
                 const bool pair = walk.careful;
                 const int32_t tA = walk.ticket, tB = walk.next_ticket;
-                const int32_t j_end = pair ? 2 * kBatch : kBatch;
-                int32_t j_from = kBatch;               // first slot of tA to walk again
+                const int32_t j_end = pair ? 2 * a.batch : a.batch;
+                int32_t j_from = a.batch;               // first slot of tA to walk again
                 if (redo_cur)
-                    for (int32_t j = 0; j < kBatch; ++j)
+                    for (int32_t j = 0; j < a.batch; ++j)
                         if (ticket_tile(a, tA, j) == tile) j_from = j;
                 redo_cur = false;
                 // slot j_from itself is published (it is this iteration's tile); when tA is used up
                 // (j_from = kBatch) every slot of tB is still to be counted
 #pragma unroll 1
-                for (int32_t j = j_from < kBatch ? j_from + 1 : kBatch; j < j_end; ++j) {
-                    const int32_t t = j < kBatch ? ticket_tile(a, tA, j) : ticket_tile(a, tB, j - kBatch);
+                for (int32_t j = j_from < a.batch ? j_from + 1 : a.batch; j < j_end; ++j) {
+                    const int32_t t = j < a.batch ? ticket_tile(a, tA, j) : ticket_tile(a, tB, j - a.batch);
                     if (t >= 0) publish_count(t);
                 }
                 __syncthreads();
@@ -2064,10 +2085,12 @@ int static_scratch(void **ptr, size_t *bytes) {
 #endif
 
 int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *refresh, int arith, int resident,
-                  int worker_cap, int adjacent, void *stream) {
+                  int worker_cap, int order, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     EncodeArgs a = args;
-    a.adjacent = adjacent ? 1 : 0;
+    a.adjacent = order == ROSE_TILE_ORDER_SPREAD ? 0 : 1;
+    a.timed = order == ROSE_TILE_ORDER_TIMED ? 1 : 0;
+    a.batch = a.timed ? kBatchTimed : kBatch;
     if (resident < 1) return (int)hipErrorInvalidValue;
     // servers: one wave per block at most, ROSE_SERVER_WGS workgroups at most, and never more than
     // a quarter of what is resident.  They are the first workgroups of the grid, so they are
@@ -2089,7 +2112,7 @@ int launch_encode(const EncodeArgs &args, int new_is_f32, const RefreshArgs *ref
     if (workers < a.n_tiles && workers <= kBlock) return (int)hipErrorInvalidValue;   // device holds too few workgroups
     a.n_server_wgs = server_wgs;
     a.n_servers = server_wgs * kWaves;
-    a.n_tickets = ((a.n_blocks + kBatch - 1) / kBatch) * kBlock;
+    a.n_tickets = ((a.n_blocks + a.batch - 1) / a.batch) * kBlock;
     // header, tile words and block words are one array
     const int64_t n_words = (int64_t)(kWsHeaderBytes / sizeof(u64)) + a.n_tiles + a.n_blocks;
     int reset_blocks = (int)((n_words + 1023) / 1024);

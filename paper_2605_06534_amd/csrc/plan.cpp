@@ -312,7 +312,7 @@ extern "C" rose_status rose_plan_tensor_is_read(const rose_plan *p, int32_t t, u
 }
 
 extern "C" rose_status rose_plan_set_tile_order(rose_plan *p, int32_t order) {
-    if (!p || order < ROSE_TILE_ORDER_AUTO_PICK || order > ROSE_TILE_ORDER_NEIGHBOURS) return ROSE_ERR_ARG;
+    if (!p || order < ROSE_TILE_ORDER_AUTO_PICK || order > ROSE_TILE_ORDER_TIMED) return ROSE_ERR_ARG;
     p->tile_order.store(order, std::memory_order_relaxed);
     return ROSE_OK;
 }

@@ -84,6 +84,8 @@ struct EncodeArgs {
     int32_t n_servers;                      // waves that serve prefixes (kWaves per serving workgroup)
     int32_t n_tickets;                      // tickets the counter hands out
     int32_t adjacent;                       // a ticket's tiles are neighbours in the bucket (see ticket_tile)
+    int32_t batch;                          // tiles per ticket
+    int32_t timed;                          // bucket stores go out in shared windows of time (see encode_body)
     unsigned int *ticket;                   // workspace header: the ticket counter
 };
 
@@ -92,12 +94,18 @@ struct EncodeArgs {
 constexpr int kBlock = 64;
 
 // workspace layout (bytes): header, tile descriptors, block descriptors
-// A ticket hands a worker kBatch tiles: the tiles at one position of kBatch consecutive blocks
-// (a "group" of blocks has kBlock tickets).  All tickets come from one counter, in order.
+// A ticket hands a worker a batch of tiles: the tiles at one position of as many consecutive blocks
+// (a "group" of blocks has kBlock tickets).  All tickets come from one counter, in order.  The
+// counter serves one ticket in about 14 ns, whoever asks: with 3 tiles (96 KB of input) per ticket it
+// alone caps a launch at about 6 TB/s, which the other tile orders do not reach anyway; the timed
+// order does, and takes 4.
 #ifndef ROSE_BATCH
 #define ROSE_BATCH 3
 #endif
-constexpr int kBatch = ROSE_BATCH;
+#ifndef ROSE_BATCH_TIMED
+#define ROSE_BATCH_TIMED 4
+#endif
+constexpr int kBatch = ROSE_BATCH, kBatchTimed = ROSE_BATCH_TIMED;
 
 constexpr size_t kWsAbortOff = 0;
 constexpr int kWsCarefulWord = 2;      // 32-bit word 2 of the header counts same-group ticket pairs (diagnostic)
@@ -128,9 +136,9 @@ struct RefreshArgs {
     int32_t n;
 };
 // resident: workgroups of this kernel variant that fit on the device at once (encode_resident_all);
-// worker_cap: 0, or the most workgroups that may walk tiles
+// worker_cap: 0, or the most workgroups that may walk tiles; order: ROSE_TILE_ORDER_SPREAD, _NEIGHBOURS or _TIMED
 int launch_encode(const EncodeArgs &a, int new_is_f32, const RefreshArgs *refresh, int arith, int resident,
-                  int worker_cap, int adjacent, void *stream);
+                  int worker_cap, int order, void *stream);
 // resident workgroups of each of the eight encode kernel variants on the current device
 // (index: fp32 input + 2 * refresh + 4 * arithmetic payload)
 int encode_resident_all(int resident[8]);

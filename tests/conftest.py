@@ -29,7 +29,7 @@ def pytest_collection_modifyitems(config, items):
             item.add_marker(skip)
 
 
-@pytest.fixture(params=[1, 2], ids=["spread", "neighbours"])
+@pytest.fixture(params=[1, 2, 3], ids=["spread", "neighbours", "timed"])
 def tile_order(request, monkeypatch):
     """Runs a test once per order in which the encode kernel's workgroups take tiles (the buckets
     must be the same bytes either way): every plan the test makes gets the order set."""

@@ -312,8 +312,8 @@ def test_pipeline_plan_argument_errors():
 
 def test_tile_order_setter_checks_its_argument():
     plan = R.shard_plan([dict(name="w", rows=8, cols=8, rule=R.SPLIT_ROWS, sections=None)], 2)
-    for order in (binding.TILE_ORDER_AUTO, binding.TILE_ORDER_SPREAD, binding.TILE_ORDER_NEIGHBOURS):
+    for order in (binding.TILE_ORDER_AUTO, binding.TILE_ORDER_SPREAD, binding.TILE_ORDER_NEIGHBOURS, binding.TILE_ORDER_TIMED):
         plan.set_tile_order(order)
-    for bad in (-1, 3):
+    for bad in (-1, 4):
         with pytest.raises(R.RoseError):
             plan.set_tile_order(bad)
