@@ -188,7 +188,8 @@ rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
  * workgroup until a window of time that all workgroups share (they read one clock), so that the
  * memory sees the bucket writes in bursts instead of a steady trickle among the reads; best below
  * about 4 %.  ROSE_TILE_ORDER_AUTO_PICK (the default): the library picks, from the density of the
- * plan's previous launch as far as rose_bucket_check has read it back (spread until then).
+ * plan's previous launch as far as rose_bucket_check has read it back (until then from the share of
+ * the shards that the buckets passed in could hold at most).
  * May be called at any time from any thread; a launch uses the value it finds.
  */
 #define ROSE_TILE_ORDER_AUTO_PICK 0

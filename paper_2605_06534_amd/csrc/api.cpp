@@ -173,7 +173,14 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     // 0.5 / 1 / 2 / 3 / 4 %, 2 % slower at 5 %).
     int order = p->tile_order.load(std::memory_order_relaxed);
     if (order == ROSE_TILE_ORDER_AUTO_PICK) {
-        const int32_t ppm = p->seen_density_ppm.load(std::memory_order_relaxed);
+        int32_t ppm = p->seen_density_ppm.load(std::memory_order_relaxed);
+        if (ppm < 0 && p->capacity_sum > 0) {
+            // nothing read back yet: the buckets cannot hold more than their capacities, which bounds the density
+            double room = 0;
+            for (int32_t d = 0; d < p->n_buckets; ++d) room += (double)buckets[d].capacity;
+            const double bound = 1e6 * room / (double)p->capacity_sum;
+            ppm = bound >= 1e6 ? -1 : (int32_t)bound;
+        }
         order = ppm < 0 ? ROSE_TILE_ORDER_SPREAD
                         : ppm < kTimedBelowPpm ? ROSE_TILE_ORDER_TIMED
                                                : ppm < kNeighboursBelowPpm ? ROSE_TILE_ORDER_NEIGHBOURS : ROSE_TILE_ORDER_SPREAD;
