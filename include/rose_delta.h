@@ -197,6 +197,12 @@ rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
 #define ROSE_TILE_ORDER_NEIGHBOURS 2
 #define ROSE_TILE_ORDER_TIMED 3
 rose_status rose_plan_set_tile_order(rose_plan *plan, int32_t order);
+/*
+ * The order an encode launch into `buckets` (HOST array of rose_plan_n_buckets structs; only the
+ * capacities are read) would use at this moment: the order set, or the library's pick.  Host only.
+ * ROSE_ERR_ARG for null pointers.
+ */
+rose_status rose_plan_pick_tile_order(const rose_plan *plan, const rose_bucket *buckets, int32_t *order);
 
 /* Host queries on a plan (no GPU needed). */
 int32_t rose_plan_n_tensors(const rose_plan *plan);

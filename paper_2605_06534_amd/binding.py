@@ -50,6 +50,7 @@ _SIGS = {
     "rose_plan_n_tensors": (_i32, [_vp]),
     "rose_plan_tp": (_i32, [_vp]),
     "rose_plan_n_buckets": (_i32, [_vp]),
+    "rose_plan_pick_tile_order": (_i32, [_vp, _vp, _P(_i32)]),
     "rose_plan_stage_of": (_i32, [_vp, _i32, _P(_i32), _P(_i32)]),
     "rose_plan_tensor_is_read": (_i32, [_vp, _i32, ctypes.c_uint32, _P(_i32)]),
     "rose_plan_tensor_base": (_i32, [_vp, _i32, _P(_i64)]),
@@ -143,6 +144,13 @@ class Plan:
 
     def set_tile_order(self, order):
         _check(_lib.rose_plan_set_tile_order(self._h, order), "plan_set_tile_order")
+
+    def pick_tile_order(self, capacities):
+        """The tile order a launch into buckets of these capacities would use now (host only)."""
+        cb = (CBucket * self.n_buckets)(*[CBucket(None, None, int(c), None) for c in capacities])
+        v = _i32()
+        _check(_lib.rose_plan_pick_tile_order(self._h, cb, ctypes.byref(v)), "plan_pick_tile_order")
+        return v.value
 
     def stage_of(self, t):
         a, b = _i32(), _i32()

@@ -120,6 +120,29 @@ extern "C" void rose_shard_plan_destroy(rose_plan *p) {
     delete p;
 }
 
+// The tile order a launch into these buckets uses: the caller's choice, else by density.
+static int pick_tile_order(const rose_plan *p, const rose_bucket *buckets) {
+    int order = p->tile_order.load(std::memory_order_relaxed);
+    if (order != ROSE_TILE_ORDER_AUTO_PICK) return order;
+    int32_t ppm = p->seen_density_ppm.load(std::memory_order_relaxed);
+    if (ppm < 0 && p->capacity_sum > 0) {
+        // nothing read back yet: the buckets cannot hold more than their capacities, which bounds the density
+        double room = 0;
+        for (int32_t d = 0; d < p->n_buckets; ++d) room += (double)(buckets[d].capacity > 0 ? buckets[d].capacity : 0);
+        const double bound = 1e6 * room / (double)p->capacity_sum;
+        ppm = bound >= 1e6 ? -1 : (int32_t)bound;
+    }
+    return ppm < 0 ? ROSE_TILE_ORDER_SPREAD
+                   : ppm < kTimedBelowPpm ? ROSE_TILE_ORDER_TIMED
+                                          : ppm < kNeighboursBelowPpm ? ROSE_TILE_ORDER_NEIGHBOURS : ROSE_TILE_ORDER_SPREAD;
+}
+
+extern "C" rose_status rose_plan_pick_tile_order(const rose_plan *p, const rose_bucket *buckets, int32_t *order) {
+    if (!p || !buckets || !order) return ROSE_ERR_ARG;
+    *order = pick_tile_order(p, buckets);
+    return ROSE_OK;
+}
+
 // workspace = nullptr: the library's built-in scratch (the call must not allocate)
 static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs, const void *const *new_ptrs,
                                  int32_t new_dtype, const rose_bucket *buckets, void *workspace,
@@ -171,20 +194,7 @@ static rose_status encode_common(const rose_plan *p, const void *const *old_ptrs
     // (7B-style workload, neighbours against spread on the same buffers: 2.7 / 1.8 / 1.4 / 1.0 % faster at
     // 1 / 2 / 5 / 7 %, 2 / 13 % slower at 8 / 10 %; timed against neighbours: 1.6 / 5 / 8 / 7 / 1 % faster at
     // 0.5 / 1 / 2 / 3 / 4 %, 2 % slower at 5 %).
-    int order = p->tile_order.load(std::memory_order_relaxed);
-    if (order == ROSE_TILE_ORDER_AUTO_PICK) {
-        int32_t ppm = p->seen_density_ppm.load(std::memory_order_relaxed);
-        if (ppm < 0 && p->capacity_sum > 0) {
-            // nothing read back yet: the buckets cannot hold more than their capacities, which bounds the density
-            double room = 0;
-            for (int32_t d = 0; d < p->n_buckets; ++d) room += (double)buckets[d].capacity;
-            const double bound = 1e6 * room / (double)p->capacity_sum;
-            ppm = bound >= 1e6 ? -1 : (int32_t)bound;
-        }
-        order = ppm < 0 ? ROSE_TILE_ORDER_SPREAD
-                        : ppm < kTimedBelowPpm ? ROSE_TILE_ORDER_TIMED
-                                               : ppm < kNeighboursBelowPpm ? ROSE_TILE_ORDER_NEIGHBOURS : ROSE_TILE_ORDER_SPREAD;
-    }
+    const int order = pick_tile_order(p, buckets);
     return rose::launch_encode(a, f32, refresh ? &r : nullptr, arith ? 1 : 0, resident,
                                p->worker_cap.load(std::memory_order_relaxed), order, stream) == 0
                ? ROSE_OK

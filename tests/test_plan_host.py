@@ -317,3 +317,23 @@ def test_tile_order_setter_checks_its_argument():
     for bad in (-1, 4):
         with pytest.raises(R.RoseError):
             plan.set_tile_order(bad)
+
+
+def test_tile_order_is_picked_from_what_the_buckets_can_hold():
+    """Before anything is read back the library bounds the density by the buckets' capacities:
+    timed below 4 %, neighbours below 7.5 %, spread otherwise and when the buckets could hold
+    everything; an order that was set is used as it is."""
+    ts = models.decoder(2, 64, 4, 4, 16, 96, 128, fused=True)
+    plan = R.shard_plan(ts, 4)
+    full = [plan.bucket_capacity(d) for d in range(4)]
+    share = lambda f: [int(c * f) for c in full]
+    assert plan.pick_tile_order(share(0.02)) == binding.TILE_ORDER_TIMED
+    assert plan.pick_tile_order(share(0.039)) == binding.TILE_ORDER_TIMED
+    assert plan.pick_tile_order(share(0.05)) == binding.TILE_ORDER_NEIGHBOURS
+    assert plan.pick_tile_order(share(0.074)) == binding.TILE_ORDER_NEIGHBOURS
+    assert plan.pick_tile_order(share(0.08)) == binding.TILE_ORDER_SPREAD
+    assert plan.pick_tile_order(full) == binding.TILE_ORDER_SPREAD
+    assert plan.pick_tile_order([0, 0, 0, 0]) == binding.TILE_ORDER_TIMED
+    for order in (binding.TILE_ORDER_SPREAD, binding.TILE_ORDER_NEIGHBOURS, binding.TILE_ORDER_TIMED):
+        plan.set_tile_order(order)
+        assert plan.pick_tile_order(share(0.02)) == order and plan.pick_tile_order(full) == order
