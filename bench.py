@@ -356,6 +356,15 @@ def bw_probes(R, nnz_total, n_tiles, mixed, touched_lines):
         moved = (2 * big + mix_dst.numel()) * 5
         probe["encode_mix_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
         probe["encode_mix_write_bytes_per_16k_pair"] = per_chunk
+        # the same traffic with the writes held back and sent in the windows of the timed tile order
+        for _ in range(2):
+            R.bw_probe_mixed(src_a, src_b, mix_dst, per_chunk, sink, timed=True)
+        a.record()
+        for _ in range(5):
+            R.bw_probe_mixed(src_a, src_b, mix_dst, per_chunk, sink, timed=True)
+        b.record()
+        torch.cuda.synchronize()
+        probe["encode_mix_timed_writes_GBs"] = round(moved / 1e9 / (a.elapsed_time(b) / 1e3), 1)
         del mix_dst, src_a, src_b
     torch.cuda.empty_cache()
     return probe

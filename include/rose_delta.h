@@ -433,6 +433,13 @@ rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *si
 #define ROSE_PROBE_CHUNK 16384
 rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
                                 size_t write_bytes_per_chunk, uint64_t *sink, void *stream);
+/*
+ * The same traffic with the writes bunched in time: a workgroup writes the output of the chunks it
+ * has read only in the windows of time that ROSE_TILE_ORDER_TIMED uses (or when 64 chunks are due),
+ * to measure what the memory gains from taking the writes in bursts.  Same arguments and errors.
+ */
+rose_status rose_bw_probe_mixed_timed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
+                                      size_t write_bytes_per_chunk, uint64_t *sink, void *stream);
 
 /*
  * Line probe: what HBM delivers for delta_apply's access pattern without any of its work.  Reads,

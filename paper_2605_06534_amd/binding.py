@@ -75,6 +75,7 @@ _SIGS = {
     "rose_object_check": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _P(_i32), _P(_i64), _P(_i64), _P(_i32)]),
     "rose_bw_probe": (_i32, [_vp, _vp, ctypes.c_size_t, _vp, _vp]),
     "rose_bw_probe_mixed": (_i32, [_vp, _vp, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp]),
+    "rose_bw_probe_mixed_timed": (_i32, [_vp, _vp, _vp, ctypes.c_size_t, ctypes.c_size_t, _vp, _vp]),
     "rose_bw_probe_lines": (_i32, [_vp, ctypes.c_size_t, ctypes.c_uint32, _vp]),
     "rose_status_str": (ctypes.c_char_p, [_i32]),
 }
@@ -323,10 +324,12 @@ def bw_probe(src, dst=None, sink=None, stream=None):
                               sink.data_ptr() if sink is not None else None, _stream(stream)), "bw_probe")
 
 
-def bw_probe_mixed(src_a, src_b, dst, write_bytes_per_chunk, sink, stream=None):
+def bw_probe_mixed(src_a, src_b, dst, write_bytes_per_chunk, sink, stream=None, timed=False):
+    """timed: the writes go out in the windows of time of the timed tile order"""
     nbytes = src_a.numel() * src_a.element_size()
-    _check(_lib.rose_bw_probe_mixed(src_a.data_ptr(), src_b.data_ptr(), dst.data_ptr(), nbytes,
-                                    write_bytes_per_chunk, sink.data_ptr(), _stream(stream)), "bw_probe_mixed")
+    f = _lib.rose_bw_probe_mixed_timed if timed else _lib.rose_bw_probe_mixed
+    _check(f(src_a.data_ptr(), src_b.data_ptr(), dst.data_ptr(), nbytes, write_bytes_per_chunk, sink.data_ptr(),
+             _stream(stream)), "bw_probe_mixed")
 
 
 def bw_probe_lines(dst, touched_fraction, stream=None):

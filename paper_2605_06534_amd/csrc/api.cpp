@@ -306,16 +306,26 @@ extern "C" rose_status rose_bw_probe(const void *src, void *dst, size_t bytes, u
     return rose::launch_bw_probe(src, dst, bytes, sink, stream) == 0 ? ROSE_OK : ROSE_ERR_HIP;
 }
 
-extern "C" rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
-                                           size_t write_bytes_per_chunk, uint64_t *sink, void *stream) {
+static rose_status probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
+                               size_t write_bytes_per_chunk, int timed, uint64_t *sink, void *stream) {
     if (!src_a || !src_b || !dst || !sink) return ROSE_ERR_ARG;
     if ((read_bytes % ROSE_PROBE_CHUNK) || (write_bytes_per_chunk & 15u) || write_bytes_per_chunk > ROSE_PROBE_CHUNK)
         return ROSE_ERR_ARG;
     if (!aligned(src_a, 16) || !aligned(src_b, 16) || !aligned(dst, 16) || !aligned(sink, 8)) return ROSE_ERR_ALIGN;
     return rose::launch_bw_probe_mixed(src_a, src_b, dst, read_bytes / ROSE_PROBE_CHUNK,
-                                       (uint32_t)(write_bytes_per_chunk / 16), sink, stream) == 0
+                                       (uint32_t)(write_bytes_per_chunk / 16), timed, sink, stream) == 0
                ? ROSE_OK
                : ROSE_ERR_HIP;
+}
+
+extern "C" rose_status rose_bw_probe_mixed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
+                                           size_t write_bytes_per_chunk, uint64_t *sink, void *stream) {
+    return probe_mixed(src_a, src_b, dst, read_bytes, write_bytes_per_chunk, 0, sink, stream);
+}
+
+extern "C" rose_status rose_bw_probe_mixed_timed(const void *src_a, const void *src_b, void *dst, size_t read_bytes,
+                                                 size_t write_bytes_per_chunk, uint64_t *sink, void *stream) {
+    return probe_mixed(src_a, src_b, dst, read_bytes, write_bytes_per_chunk, 1, sink, stream);
 }
 
 extern "C" rose_status rose_bw_probe_lines(void *dst, size_t bytes, uint32_t touched_per_2_32, void *stream) {

@@ -1969,10 +1969,21 @@ __global__ __launch_bounds__(256) void bw_read_kernel(const uint4 *src, size_t n
 
 // Mixed probe: the traffic of an encode launch without any of its work.  Reads two streams in
 // 16 KB chunks (non-temporal, like encode) and writes w16 16-byte vectors per chunk, contiguous
-// across chunks, to a third.
+// across chunks, to a third.  TIMED = 0: every chunk's output is written at once.  TIMED = 1: it is
+// held back (nothing is stored anywhere: the probe only remembers which chunks are due) and written
+// in the windows of time of the encode kernel's timed tile order, or when 64 chunks are due.
+template <int TIMED>
 __global__ __launch_bounds__(256) void bw_mix_kernel(const uint4 *a, const uint4 *b, uint4 *dst, size_t n_chunks,
                                                      uint32_t w16, u64 *sink) {
     uint4 acc = make_uint4(0, 0, 0, 0);
+    size_t due_from = blockIdx.x;                      // the oldest chunk whose output has not been written
+    uint32_t n_due = 0;
+    auto write_chunk = [&](size_t c) {
+        for (uint32_t k = threadIdx.x; k < w16; k += kBwThreads) {
+            u32x4 w = {acc.x, acc.y, acc.z, acc.w};
+            __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(dst + c * (size_t)w16 + k)));
+        }
+    };
     for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         uint4 va[4], vb[4];
 #pragma unroll
@@ -1982,11 +1993,19 @@ __global__ __launch_bounds__(256) void bw_mix_kernel(const uint4 *a, const uint4
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc = xor4(acc, xor4(va[j], vb[j]));
-        for (uint32_t k = threadIdx.x; k < w16; k += kBwThreads) {
-            u32x4 w = {acc.x, acc.y, acc.z, acc.w};
-            __builtin_nontemporal_store(w, reinterpret_cast<global_u32x4 *>(reinterpret_cast<uintptr_t>(dst + c * (size_t)w16 + k)));
+        if (!TIMED) {
+            write_chunk(c);
+        } else {
+            ++n_due;
+            const uint32_t now = (uint32_t)__builtin_amdgcn_s_memrealtime();
+            const bool open = (now & ((1u << ROSE_WRITE_PERIOD_LOG2) - 1u)) < (1u << ROSE_WRITE_OPEN_LOG2);
+            if (open || n_due >= 64u) {
+                for (; n_due > 0; --n_due, due_from += gridDim.x) write_chunk(due_from);
+            }
         }
     }
+    if (TIMED)
+        for (; n_due > 0; --n_due, due_from += gridDim.x) write_chunk(due_from);
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) atomicAdd(sink, 1ull);
 }
 
@@ -2207,14 +2226,19 @@ int launch_bw_probe_lines(void *dst, size_t n_lines, uint32_t threshold, void *s
     return (int)hipGetLastError();
 }
 
-int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, uint64_t *sink,
-                          void *stream) {
+int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, int timed,
+                          uint64_t *sink, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_chunks == 0) return 0;
     int blocks = n_chunks > 256 * 32 ? 256 * 32 : (int)n_chunks;
-    hipLaunchKernelGGL(bw_mix_kernel, dim3(blocks), dim3(kBwThreads), 0, st, static_cast<const uint4 *>(a),
-                       static_cast<const uint4 *>(b), static_cast<uint4 *>(dst), n_chunks, w16,
-                       reinterpret_cast<u64 *>(sink));
+    if (timed)
+        hipLaunchKernelGGL(bw_mix_kernel<1>, dim3(blocks), dim3(kBwThreads), 0, st, static_cast<const uint4 *>(a),
+                           static_cast<const uint4 *>(b), static_cast<uint4 *>(dst), n_chunks, w16,
+                           reinterpret_cast<u64 *>(sink));
+    else
+        hipLaunchKernelGGL(bw_mix_kernel<0>, dim3(blocks), dim3(kBwThreads), 0, st, static_cast<const uint4 *>(a),
+                           static_cast<const uint4 *>(b), static_cast<uint4 *>(dst), n_chunks, w16,
+                           reinterpret_cast<u64 *>(sink));
     return (int)hipGetLastError();
 }
 

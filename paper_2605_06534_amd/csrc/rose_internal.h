@@ -162,8 +162,8 @@ size_t object_bytes_for(int32_t n_tensors, int64_t n);
 bool object_header_valid(const uint32_t *header, int32_t n_tensors, size_t object_bytes, int64_t *n);
 int launch_bw_probe(const void *src, void *dst, size_t bytes, uint64_t *sink, void *stream);
 int launch_bw_probe_lines(void *dst, size_t n_lines, uint32_t threshold, void *stream);
-int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, uint64_t *sink,
-                          void *stream);
+int launch_bw_probe_mixed(const void *a, const void *b, void *dst, size_t n_chunks, uint32_t w16, int timed,
+                          uint64_t *sink, void *stream);
 
 }  // namespace rose
 

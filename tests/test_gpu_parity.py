@@ -271,6 +271,13 @@ def test_bandwidth_probes_move_what_they_say():
         for j in range(4):
             want ^= av[c * 1024 + j * 256] ^ bv[c * 1024 + j * 256]
         assert np.array_equal(dst[c * per_chunk:c * per_chunk + 16].cpu().numpy(), want), c
+    # the timed variant writes the same places (what it writes is whatever the thread has read by then)
+    av0 = dst[:4 * per_chunk].clone()
+    dst.fill_(0x5A)
+    R.bw_probe_mixed(a, b, dst, per_chunk, sink, timed=True)
+    torch.cuda.synchronize()
+    assert bool((dst[4 * per_chunk:] == 0x5A).all()), "the timed mixed probe wrote past its output"
+    assert torch.equal(dst[:4 * per_chunk], av0)       # one chunk per workgroup: due and written at once or at the end
     # the line probe changes whole 64-byte lines, about the stated share of them, first word of each
     # 16-byte part incremented, everything else as it was
     buf = torch.zeros(1 << 22, dtype=torch.int32, device="cuda")            # 16 MiB = 262,144 lines
