@@ -183,8 +183,8 @@ rose_status rose_plan_set_worker_cap(rose_plan *plan, int32_t workers);
  * are the same bytes either way).  ROSE_TILE_ORDER_SPREAD: a workgroup takes tiles that lie 64 tiles
  * apart, so that the prefix sums across workgroups are ready soonest; best above about 7.5 % of changed
  * elements.  ROSE_TILE_ORDER_NEIGHBOURS: it takes three neighbouring tiles and writes their entries
- * as one run, which shares fewer 64-byte lines of the bucket with other workgroups; best at low
- * densities.  ROSE_TILE_ORDER_TIMED: four neighbouring tiles, and the entries are held in the
+ * as one run, which shares fewer 64-byte lines of the bucket with other workgroups; best between
+ * about 4 and 7.5 %.  ROSE_TILE_ORDER_TIMED: four neighbouring tiles, and the entries are held in the
  * workgroup until a window of time that all workgroups share (they read one clock), so that the
  * memory sees the bucket writes in bursts instead of a steady trickle among the reads; best below
  * about 4 %.  ROSE_TILE_ORDER_AUTO_PICK (the default): the library picks, from the density of the
