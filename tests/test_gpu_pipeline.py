@@ -78,6 +78,27 @@ def receiver_shards(ts, recs, plan, tp, which, dummy):
 def test_pipeline_senders_feed_receivers_with_another_stage_split(n_layers, tp_src, pp_src, tp, pp_dst, tile_order):
     print("case: pipeline %d layers tp_src=%d pp_src=%d -> tp=%d pp_dst=%d" % (n_layers, tp_src, pp_src, tp, pp_dst), flush=True)
     ts, recs = model(n_layers, seed=40 + pp_src, p=0.08)
+    senders_feed_receivers(ts, recs, n_layers, tp_src, pp_src, tp, pp_dst)
+
+
+def test_paper_example_at_full_width():
+    """Sec. 4.2's example, training TP8 x PP2 -> serving TP4, on the 32B-style attention shapes at full
+    width (hidden 5120, 40 query and 8 KV heads of 128: one KV head per sender; two layers, one per
+    sending stage; the feed-forward width and the vocabulary cut to an eighth and a thirty-second to
+    keep the host-side slicing short): every one of the 16 senders' buckets against the oracle, the
+    receivers against numpy slices."""
+    print("case: pipeline, 32B-style shapes, tp_src=8 pp_src=2 -> tp=4 pp_dst=1", flush=True)
+    n_layers = 2
+    ts = models.decoder(n_layers, 5120, 40, 8, 128, 27648 // 8, 152064 // 32, fused=True)
+    recs = []
+    for _, t, o, n in synth.model_pairs(ts, "bernoulli", 61, "cuda", p=0.02):       # drawn on the device, kept on the host
+        recs.append(dict(t, old=bits(o), new=bits(n)))
+        del o, n
+    torch.cuda.empty_cache()
+    senders_feed_receivers(ts, recs, n_layers, 8, 2, 4, 1)
+
+
+def senders_feed_receivers(ts, recs, n_layers, tp_src, pp_src, tp, pp_dst):
     dummy = torch.zeros(64, dtype=torch.int16, device="cuda")
     # the receivers know nothing of the senders' split: their plan is made with one sending stage
     rplan = R.shard_plan(ts, tp, 1, 0, n_layers, 1, 0, pp_dst)
